@@ -1,0 +1,155 @@
+/*
+ * dcasgd.h - C ABI of the MI355X (gfx950) DC-ASGD parameter-server update.
+ *
+ * The library implements the server side of "Asynchronous Stochastic Gradient
+ * Descent with Delay Compensation" (Zheng et al.): Algorithm 2 with the update
+ * rule of Eq. 4.1, with a constant lambda (DC-ASGD-c) or the adaptive lambda
+ * of Eq. 18 (DC-ASGD-a).  Every step runs in hand-written HIP kernels; the
+ * library allocates no device memory and owns nothing but the small handle.
+ *
+ * Conventions
+ *   - "device pointer": memory of the GPU that is current when the call is
+ *     made, owned by the caller and kept alive until the stream has passed the
+ *     call.  "host pointer": ordinary process memory, read during the call.
+ *   - stream: a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it and returns immediately; calls on one handle must
+ *     be issued from one thread at a time and are ordered by the stream.
+ *   - State vectors are float32.  w, ms and every backup row must be 16-byte
+ *     aligned; bak_stride (in elements) must be a multiple of 4 and >= d.
+ *   - No call throws or aborts.  int-returning calls return DCASGD_OK or a
+ *     negative DCASGD_E* code; pointer-returning calls return NULL and leave
+ *     the code in dcasgd_last_error().  Arguments are validated on the host
+ *     before anything is launched; a rejected call launches nothing.
+ *   - Arithmetic: IEEE binary32, one rounding per operation, no fused
+ *     multiply-add, correctly rounded sqrt and division, denormals kept; the
+ *     operation order is the one written next to each entry point.
+ */
+#ifndef DCASGD_H
+#define DCASGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dcasgd_server* dcasgd_t;
+
+/* mode argument of dcasgd_create: one variant, optionally OR-ed with flags */
+enum {
+    DCASGD_MODE_C       = 0,       /* lambda_t = lambda0 (Section 6, "DC-ASGD-c")          */
+    DCASGD_MODE_A       = 1,       /* lambda_t = lambda0/sqrt(MeanSquare(t)+eps), Eq. 18   */
+    DCASGD_GRAD_BF16    = 1 << 4,  /* pushed gradients are bfloat16 (2 bytes per element)  */
+    DCASGD_PULL_ON_PUSH = 1 << 5   /* every push also refreshes the pusher's backup        */
+};
+
+enum {
+    DCASGD_OK      =  0,
+    DCASGD_EINVAL  = -1,  /* bad handle, worker id, K, mode, hyper-parameter, NULL pointer, overlap */
+    DCASGD_EALIGN  = -2,  /* a pointer or stride breaks the alignment rules above                   */
+    DCASGD_ESTATE  = -3,  /* call needs dcasgd_bind / dcasgd_init first                             */
+    DCASGD_EHIP    = -4   /* the HIP runtime reported an error at launch                            */
+};
+
+#define DCASGD_MAX_K 16   /* longest queue one dcasgd_push_batch call accepts */
+
+/*
+ * Create a server for d parameters and M workers (Algorithm 2, "Input").
+ * eta: learning rate; lambda0: lambda of Eq. 4.1 (MODE_C) or lambda_0 of
+ * Eq. 18 (MODE_A); ema_m: the constant m of Eq. 18, in [0,1) (ignored in
+ * MODE_C); eps: the epsilon under the square root (>= 0).
+ * Returns NULL if d == 0, M <= 0, the mode is unknown, ema_m is outside
+ * [0,1), or a hyper-parameter is not finite.  No GPU call is made.
+ */
+dcasgd_t dcasgd_create(size_t d, int M, float eta, float lambda0, int mode,
+                       float ema_m, float eps);
+
+/* Free the handle (host memory only).  Bound device memory stays the caller's. */
+int dcasgd_destroy(dcasgd_t h);
+
+/*
+ * Attach caller-owned device memory: w[d] (global model), bak (M rows of
+ * bak_stride floats; row m is w_bak(m) of Algorithm 2), ms[d] (MeanSquare of
+ * Eq. 18; may be NULL in MODE_C).  The ranges must not overlap.
+ */
+int dcasgd_bind(dcasgd_t h, float* w, float* bak, size_t bak_stride, float* ms);
+
+/*
+ * Algorithm 2, "Initialize": w_bak(m) <- w for every m, MeanSquare <- 0,
+ * t <- 0.  w must already hold w_0.  Enqueued on stream.
+ */
+int dcasgd_init(dcasgd_t h, void* stream);
+
+/*
+ * Algorithm 2, "receive g_m": apply one pushed gradient (device pointer, d
+ * elements, float32 or bfloat16 per DCASGD_GRAD_BF16, 16-byte aligned;
+ * 8-byte for bfloat16).  Per element, in this order (b = w_bak(worker)):
+ *   MODE_A only: g2 = g*g; t1 = ema_m*ms; t2 = (1-ema_m)*g2; ms = t1+t2;
+ *                den = ms+eps; rt = sqrt(den); lam = lambda0/rt
+ *   diff = w-b; g2 = g*g; c1 = lam*g2 (lambda0*g2 in MODE_C); c2 = c1*diff;
+ *   gd = g+c2; st = eta*gd; w = w-st                                (Eq. 4.1)
+ * then t <- t+1.  With DCASGD_PULL_ON_PUSH the same pass also stores
+ * w_bak(worker) <- w (the pull that follows a push in Algorithm 1).
+ */
+int dcasgd_push(dcasgd_t h, int worker, const void* grad, void* stream);
+
+/*
+ * A queue of K pushes, 1 <= K <= DCASGD_MAX_K, defined as
+ *   for k in 0..K-1: push(workers[k], grads[k]); pull(workers[k])
+ * and computed in one pass per element with w and ms held in registers.
+ * workers and grads are host arrays of K entries (grads[k]: device pointer
+ * as for dcasgd_push).  A queue that repeats a worker is legal: it is split
+ * into consecutive launches at each repeat so that the later push sees the
+ * refreshed backup.
+ */
+int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads,
+                      int K, void* stream);
+
+/*
+ * Algorithm 2, "pull request": w_bak(worker) <- w, enqueued on the stream of
+ * the most recent init/push on this handle, and returns the device pointer of
+ * that backup row, which is what "send w_t back to worker m" hands over.  If
+ * the row already equals w (nothing was pushed since it was last refreshed)
+ * nothing is launched.  NULL on error.
+ */
+const float* dcasgd_pull(dcasgd_t h, int worker);
+
+/* Number of pushes applied so far (the t of Algorithm 2). */
+uint64_t dcasgd_step(dcasgd_t h);
+
+/* Code of the most recent failed call on this handle (DCASGD_OK if none). */
+int dcasgd_last_error(dcasgd_t h);
+
+/* Static, human-readable text for a status code. */
+const char* dcasgd_strerror(int code);
+
+/*
+ * Launch shape used by this handle's kernels.  threads: 64..512, a multiple
+ * of 64; items: float4 groups per thread, one of 1, 2, 4; max_blocks: 0 = one
+ * block per tile, otherwise blocks loop over tiles; streaming: non-zero marks
+ * gradient reads and backup reads/writes non-temporal.  A zero/negative
+ * threads or items keeps the current value.
+ */
+int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming);
+
+/*
+ * Stand-in for Algorithm 1's "compute gradient" on a synthetic diagonal
+ * quadratic (not from the paper): for i < d
+ *   dd = snap[i]-wstar[i]; p = hdiag[i]*dd; nz = sigma*z_i; g = p+nz
+ * where z_i is a standard normal drawn from Philox4x32-10 (key = seed,
+ * counter = (i/4, push_idx, 0, 0), four normals per counter by Box-Muller in
+ * +,-,*,/,sqrt only).  grad_out: float32[d], or bfloat16[d] (round to nearest
+ * even) when as_bf16 != 0.  All pointers are device pointers, 16-byte aligned
+ * (grad_out 8-byte for bfloat16).  threads/items as in dcasgd_set_launch
+ * (0 = defaults).
+ */
+int dcasgd_synth_grad(const float* snap, const float* hdiag, const float* wstar,
+                      float sigma, uint64_t seed, uint32_t push_idx,
+                      void* grad_out, int as_bf16, size_t d, void* stream,
+                      int threads, int items);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCASGD_H */

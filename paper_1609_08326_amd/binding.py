@@ -1,0 +1,180 @@
+"""ctypes binding over ``libdcasgd.so`` (the C ABI of ``include/dcasgd.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory (``torch.empty(device="cuda")``) and
+the stream handle; nothing here computes on tensors.  There is no fallback:
+if the library is missing or a call is rejected, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdcasgd.so")
+
+MODE_C = 0
+MODE_A = 1
+GRAD_BF16 = 1 << 4
+PULL_ON_PUSH = 1 << 5
+MAX_K = 16
+
+OK, EINVAL, EALIGN, ESTATE, EHIP = 0, -1, -2, -3, -4
+
+# name -> (restype, argtypes); mirrors include/dcasgd.h one to one
+_PROTOTYPES = {
+    "dcasgd_create": (C.c_void_p, [C.c_size_t, C.c_int, C.c_float, C.c_float, C.c_int,
+                                   C.c_float, C.c_float]),
+    "dcasgd_destroy": (C.c_int, [C.c_void_p]),
+    "dcasgd_bind": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dcasgd_init": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "dcasgd_push": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
+    "dcasgd_push_batch": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_void_p),
+                                    C.c_int, C.c_void_p]),
+    "dcasgd_pull": (C.c_void_p, [C.c_void_p, C.c_int]),
+    "dcasgd_step": (C.c_uint64, [C.c_void_p]),
+    "dcasgd_last_error": (C.c_int, [C.c_void_p]),
+    "dcasgd_strerror": (C.c_char_p, [C.c_int]),
+    "dcasgd_set_launch": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "dcasgd_synth_grad": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_uint64,
+                                    C.c_uint32, C.c_void_p, C.c_int, C.c_size_t, C.c_void_p,
+                                    C.c_int, C.c_int]),
+}
+
+_lib = None
+
+
+class DcasgdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, strerror(code), code))
+
+
+def load() -> C.CDLL:
+    """Open the built library.  torch is imported first so that the HIP runtime
+    the library resolves against is the one that owns torch's allocations."""
+    global _lib
+    if _lib is None:
+        import torch  # noqa: F401  (loads libamdhip64 before our library asks for it)
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is not built; run `python -m paper_1609_08326_amd.build`" % LIB_PATH)
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in _PROTOTYPES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return load().dcasgd_strerror(int(code)).decode()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != OK:
+        raise DcasgdError(rc, where)
+
+
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def synth_grad(snap, hdiag, wstar, sigma: float, seed: int, push_idx: int, out, stream=None,
+               threads: int = 0, items: int = 0) -> None:
+    """Launch the synthetic worker kernel: out <- h*(snap-wstar) + sigma*z(seed, push_idx, i).
+    ``out`` is a float32 or bfloat16 CUDA tensor of snap's length."""
+    import torch
+    d = snap.numel()
+    assert hdiag.numel() == d and wstar.numel() == d and out.numel() == d
+    assert snap.dtype == hdiag.dtype == wstar.dtype == torch.float32
+    assert out.dtype in (torch.float32, torch.bfloat16)
+    rc = load().dcasgd_synth_grad(snap.data_ptr(), hdiag.data_ptr(), wstar.data_ptr(),
+                                  float(sigma), int(seed), int(push_idx), out.data_ptr(),
+                                  int(out.dtype == torch.bfloat16), d, _stream_ptr(stream),
+                                  int(threads), int(items))
+    _check(rc, "dcasgd_synth_grad")
+
+
+class Server:
+    """One DC-ASGD parameter server (Algorithm 2) whose state lives in torch-owned HBM.
+
+    ``w0`` is a float32 CUDA tensor holding the initial model; it becomes the
+    live model ``self.w``.  ``self.bak`` is the M x stride backup matrix (row m
+    is the snapshot worker m last pulled), ``self.ms`` the MeanSquare vector.
+    """
+
+    def __init__(self, w0, M: int, eta: float, lambda0: float, mode: int,
+                 ema_m: float = 0.0, eps: float = 0.0, grad_bf16: bool = False,
+                 pull_on_push: bool = False, stream=None):
+        import torch
+        lib = load()
+        assert w0.is_cuda and w0.dtype == torch.float32 and w0.dim() == 1 and w0.is_contiguous()
+        self.d, self.M = int(w0.numel()), int(M)
+        self.mode = int(mode)
+        self.grad_dtype = torch.bfloat16 if grad_bf16 else torch.float32
+        flags = self.mode | (GRAD_BF16 if grad_bf16 else 0) | (PULL_ON_PUSH if pull_on_push else 0)
+        self._h = lib.dcasgd_create(self.d, self.M, float(eta), float(lambda0), flags,
+                                    float(ema_m), float(eps))
+        if not self._h:
+            raise DcasgdError(EINVAL, "dcasgd_create")
+        self.stride = (self.d + 63) // 64 * 64          # rows start 256-byte aligned
+        self.w = w0
+        self.bak = torch.empty((self.M, self.stride), dtype=torch.float32, device=w0.device)
+        self.ms = torch.empty(self.d, dtype=torch.float32, device=w0.device) \
+            if self.mode == MODE_A else None
+        _check(lib.dcasgd_bind(self._h, self.w.data_ptr(), self.bak.data_ptr(), self.stride,
+                               self.ms.data_ptr() if self.ms is not None else None),
+               "dcasgd_bind")
+        _check(lib.dcasgd_init(self._h, _stream_ptr(stream)), "dcasgd_init")
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            load().dcasgd_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def t(self) -> int:
+        return int(load().dcasgd_step(self._h))
+
+    def set_launch(self, threads: int = 0, items: int = 0, max_blocks: int = 0,
+                   streaming: bool = True) -> None:
+        _check(load().dcasgd_set_launch(self._h, int(threads), int(items), int(max_blocks),
+                                        int(bool(streaming))), "dcasgd_set_launch")
+
+    def push(self, worker: int, grad, stream=None) -> None:
+        assert grad.is_cuda and grad.dtype == self.grad_dtype and grad.numel() == self.d
+        _check(load().dcasgd_push(self._h, int(worker), grad.data_ptr(), _stream_ptr(stream)),
+               "dcasgd_push")
+
+    def push_batch(self, workers: Sequence[int], grads: Sequence, stream=None) -> None:
+        K = len(workers)
+        assert K == len(grads)
+        for g in grads:
+            assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
+        wa = (C.c_int * K)(*[int(m) for m in workers])
+        ga = (C.c_void_p * K)(*[g.data_ptr() for g in grads])
+        _check(load().dcasgd_push_batch(self._h, wa, ga, K, _stream_ptr(stream)),
+               "dcasgd_push_batch")
+
+    def pull(self, worker: int):
+        """Refresh worker's backup from w and return it (a view of row `worker`)."""
+        ptr = load().dcasgd_pull(self._h, int(worker))
+        if not ptr:
+            raise DcasgdError(load().dcasgd_last_error(self._h), "dcasgd_pull")
+        row = self.bak[int(worker), : self.d]
+        assert row.data_ptr() == ptr
+        return row
+
+    def snapshot(self, worker: int):
+        """The backup row of `worker` as it stands (no refresh)."""
+        return self.bak[int(worker), : self.d]

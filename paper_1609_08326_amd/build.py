@@ -1,0 +1,42 @@
+"""Compile the HIP library for gfx950 (``hipcc`` cross-compiles without a GPU)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(_PKG, "csrc")
+SOURCES = [os.path.join(CSRC, "dcasgd.hip")]
+DEPENDS = SOURCES + [os.path.join(CSRC, "dcasgd_kernels.hip.h"),
+                     os.path.join(os.path.dirname(_PKG), "include", "dcasgd.h")]
+LIB = os.path.join(_PKG, "libdcasgd.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# -ffp-contract=off: one rounding per operation (the results are compared bit
+# for bit with a CPU build).  Packed FP32 instructions are switched off.
+HIPFLAGS = ["--offload-arch=gfx950", "-std=c++17", "-O3", "-ffp-contract=off",
+            "-fPIC", "-shared", "-Wall",
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    return any(os.path.getmtime(p) > built for p in DEPENDS)
+
+
+def build_library(force: bool = True, verbose: bool = False) -> str:
+    """Build ``libdcasgd.so`` next to this file and return its path."""
+    if force or is_stale():
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        cmd = [HIPCC, *HIPFLAGS, *SOURCES, "-o", tmp]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(force=True, verbose=True))

@@ -1,0 +1,328 @@
+// Host side of the C ABI declared in include/dcasgd.h: argument validation,
+// bookkeeping of Algorithm 2's counter t and of which backups are current,
+// and kernel launches.  No device memory is allocated here.
+#include "../../include/dcasgd.h"
+
+#include <cmath>
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "dcasgd_kernels.hip.h"
+
+using namespace dcasgd;
+
+struct dcasgd_server {
+    size_t d = 0;
+    int M = 0;
+    Hyper hp{};
+    bool adaptive = false, grad_bf16 = false, pull_on_push = false;
+    float* w = nullptr;
+    float* bak = nullptr;
+    size_t bak_stride = 0;
+    float* ms = nullptr;
+    bool bound = false, ready = false;
+    hipStream_t stream = nullptr;     // stream of the most recent init/push
+    uint64_t t = 0;                   // pushes applied (Algorithm 2's t)
+    std::vector<uint64_t> fresh_at;   // t at which w_bak(m) was last set to w
+    int threads = 256, items = 2, max_blocks = 0;
+    bool streaming = true;
+    int last_error = DCASGD_OK;
+};
+
+namespace {
+
+inline int fail(dcasgd_t h, int code) {
+    if (h) h->last_error = code;
+    return code;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+inline bool valid_threads(int t) { return t >= 64 && t <= 512 && t % 64 == 0; }
+inline bool valid_items(int i) { return i == 1 || i == 2 || i == 4; }
+
+template <class F> inline void with_bool(bool v, F&& f) {
+    if (v) f(std::true_type{}); else f(std::false_type{});
+}
+template <class F> inline void with_items(int v, F&& f) {
+    switch (v) {
+        case 1: f(std::integral_constant<int, 1>{}); break;
+        case 2: f(std::integral_constant<int, 2>{}); break;
+        default: f(std::integral_constant<int, 4>{}); break;
+    }
+}
+
+// blocks needed so that every tile of `per_block` float4 groups is covered
+inline unsigned grid_for(size_t n4, size_t per_block, int max_blocks) {
+    size_t tiles = (n4 + per_block - 1) / per_block;
+    if (tiles == 0) tiles = 1;                       // the ragged tail still needs block 0
+    if (max_blocks > 0 && tiles > (size_t)max_blocks) tiles = (size_t)max_blocks;
+    if (tiles > 0x7FFFFFFFull) tiles = 0x7FFFFFFFull; // blocks loop over tiles anyway
+    return (unsigned)tiles;
+}
+
+inline int launched(dcasgd_t h) {
+    return hipGetLastError() == hipSuccess ? DCASGD_OK : fail(h, DCASGD_EHIP);
+}
+
+inline size_t grad_bytes(const dcasgd_server* h) { return h->d * (h->grad_bf16 ? 2 : 4); }
+
+int check_grad(dcasgd_t h, const void* grad) {
+    if (!grad) return DCASGD_EINVAL;
+    if (!aligned(grad, h->grad_bf16 ? 8 : 16)) return DCASGD_EALIGN;
+    const size_t gb = grad_bytes(h);
+    if (overlaps(grad, gb, h->w, h->d * 4) ||
+        overlaps(grad, gb, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+        (h->ms && overlaps(grad, gb, h->ms, h->d * 4)))
+        return DCASGD_EINVAL;
+    return DCASGD_OK;
+}
+
+void launch_pull(dcasgd_t h, int worker, hipStream_t s) {
+    const size_t n4 = h->d / 4;
+    float* row = h->bak + (size_t)worker * h->bak_stride;
+    const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
+    with_items(h->items, [&](auto IT) {
+        with_bool(h->streaming, [&](auto NT) {
+            hipLaunchKernelGGL((pull_kernel<decltype(IT)::value, decltype(NT)::value>),
+                               dim3(grid), dim3(h->threads), 0, s, h->w, row, n4, h->d);
+        });
+    });
+}
+
+void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipStream_t s) {
+    const size_t n4 = h->d / 4;
+    float* row = h->bak + (size_t)worker * h->bak_stride;
+    const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
+    with_bool(h->adaptive, [&](auto AD) {
+      with_bool(h->grad_bf16, [&](auto BF) {
+        with_bool(fuse_pull, [&](auto PL) {
+          with_items(h->items, [&](auto IT) {
+            with_bool(h->streaming, [&](auto NT) {
+                hipLaunchKernelGGL((push_kernel<decltype(AD)::value, decltype(BF)::value,
+                                                decltype(PL)::value, decltype(IT)::value,
+                                                decltype(NT)::value>),
+                                   dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row,
+                                   grad, n4, h->d);
+            });
+          });
+        });
+      });
+    });
+}
+
+// entries [k0, k1) of a queue; their workers are pairwise distinct
+void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int k0, int k1,
+                  hipStream_t s) {
+    BatchArgs a{};
+    a.K = k1 - k0;
+    for (int k = k0; k < k1; ++k) {
+        a.grad[k - k0] = grads[k];
+        a.bak[k - k0] = h->bak + (size_t)workers[k] * h->bak_stride;
+    }
+    const size_t n4 = h->d / 4;
+    const int threads = h->threads > 256 ? 256 : h->threads;
+    const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
+    with_bool(h->adaptive, [&](auto AD) {
+      with_bool(h->grad_bf16, [&](auto BF) {
+        with_bool(h->streaming, [&](auto NT) {
+            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(BF)::value, 4,
+                                                  decltype(NT)::value>),
+                               dim3(grid), dim3(threads), 0, s, h->hp, h->w, h->ms, a, n4, h->d);
+        });
+      });
+    });
+}
+
+}  // namespace
+
+extern "C" {
+
+dcasgd_t dcasgd_create(size_t d, int M, float eta, float lambda0, int mode, float ema_m,
+                       float eps) {
+    const int variant = mode & 0xF;
+    const int flags = mode & ~0xF;
+    if (d == 0 || M <= 0) return nullptr;
+    if (variant != DCASGD_MODE_C && variant != DCASGD_MODE_A) return nullptr;
+    if (flags & ~(DCASGD_GRAD_BF16 | DCASGD_PULL_ON_PUSH)) return nullptr;
+    if (!std::isfinite(eta) || !std::isfinite(lambda0) || !std::isfinite(ema_m) ||
+        !std::isfinite(eps))
+        return nullptr;
+    if (variant == DCASGD_MODE_A && (!(ema_m >= 0.0f && ema_m < 1.0f) || eps < 0.0f))
+        return nullptr;
+    dcasgd_server* h = new (std::nothrow) dcasgd_server;
+    if (!h) return nullptr;
+    h->d = d;
+    h->M = M;
+    h->hp.eta = eta;
+    h->hp.lambda0 = lambda0;
+    h->hp.ema_m = ema_m;
+    h->hp.one_minus_m = 1.0f - ema_m;
+    h->hp.eps = eps;
+    h->adaptive = variant == DCASGD_MODE_A;
+    h->grad_bf16 = (flags & DCASGD_GRAD_BF16) != 0;
+    h->pull_on_push = (flags & DCASGD_PULL_ON_PUSH) != 0;
+    h->fresh_at.assign((size_t)M, 0);
+    return h;
+}
+
+int dcasgd_destroy(dcasgd_t h) {
+    if (!h) return DCASGD_EINVAL;
+    delete h;
+    return DCASGD_OK;
+}
+
+int dcasgd_bind(dcasgd_t h, float* w, float* bak, size_t bak_stride, float* ms) {
+    if (!h) return DCASGD_EINVAL;
+    if (!w || !bak || (h->adaptive && !ms)) return fail(h, DCASGD_EINVAL);
+    if (bak_stride < h->d) return fail(h, DCASGD_EINVAL);
+    if (!aligned(w, 16) || !aligned(bak, 16) || (ms && !aligned(ms, 16)) || bak_stride % 4 != 0)
+        return fail(h, DCASGD_EALIGN);
+    const size_t vb = h->d * 4, bb = (size_t)h->M * bak_stride * 4;
+    if (overlaps(w, vb, bak, bb) || (ms && (overlaps(ms, vb, bak, bb) || overlaps(ms, vb, w, vb))))
+        return fail(h, DCASGD_EINVAL);
+    h->w = w;
+    h->bak = bak;
+    h->bak_stride = bak_stride;
+    h->ms = ms;
+    h->bound = true;
+    h->ready = false;
+    return DCASGD_OK;
+}
+
+int dcasgd_init(dcasgd_t h, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->bound) return fail(h, DCASGD_ESTATE);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int m = 0; m < h->M; ++m) launch_pull(h, m, s);
+    if (h->ms) {
+        const size_t n4 = h->d / 4;
+        const unsigned grid = grid_for(n4, 512, 4096);
+        hipLaunchKernelGGL(fill_kernel, dim3(grid), dim3(512), 0, s, h->ms, 0.0f, n4, h->d);
+    }
+    h->stream = s;
+    h->t = 0;
+    h->fresh_at.assign((size_t)h->M, 0);
+    h->ready = true;
+    return launched(h);
+}
+
+int dcasgd_push(dcasgd_t h, int worker, const void* grad, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (worker < 0 || worker >= h->M) return fail(h, DCASGD_EINVAL);
+    if (int rc = check_grad(h, grad)) return fail(h, rc);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    launch_push(h, worker, grad, h->pull_on_push, s);
+    h->stream = s;
+    h->t += 1;
+    if (h->pull_on_push) h->fresh_at[(size_t)worker] = h->t;
+    return launched(h);
+}
+
+int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads, int K,
+                      void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (!workers || !grads || K < 1 || K > DCASGD_MAX_K) return fail(h, DCASGD_EINVAL);
+    for (int k = 0; k < K; ++k) {
+        if (workers[k] < 0 || workers[k] >= h->M) return fail(h, DCASGD_EINVAL);
+        if (int rc = check_grad(h, grads[k])) return fail(h, rc);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // cut the queue wherever a worker shows up a second time within a launch
+    int begin = 0;
+    while (begin < K) {
+        int end = begin + 1;
+        for (; end < K; ++end) {
+            bool seen = false;
+            for (int k = begin; k < end; ++k) seen = seen || workers[k] == workers[end];
+            if (seen) break;
+        }
+        launch_batch(h, workers, grads, begin, end, s);
+        begin = end;
+    }
+    h->stream = s;
+    for (int k = 0; k < K; ++k) {
+        h->t += 1;
+        h->fresh_at[(size_t)workers[k]] = h->t;
+    }
+    return launched(h);
+}
+
+const float* dcasgd_pull(dcasgd_t h, int worker) {
+    if (!h) return nullptr;
+    if (!h->ready) { fail(h, DCASGD_ESTATE); return nullptr; }
+    if (worker < 0 || worker >= h->M) { fail(h, DCASGD_EINVAL); return nullptr; }
+    const float* row = h->bak + (size_t)worker * h->bak_stride;
+    if (h->fresh_at[(size_t)worker] == h->t) return row;   // already equal to w
+    launch_pull(h, worker, h->stream);
+    h->fresh_at[(size_t)worker] = h->t;
+    if (launched(h) != DCASGD_OK) return nullptr;
+    return row;
+}
+
+uint64_t dcasgd_step(dcasgd_t h) { return h ? h->t : 0; }
+
+int dcasgd_last_error(dcasgd_t h) { return h ? h->last_error : DCASGD_EINVAL; }
+
+const char* dcasgd_strerror(int code) {
+    switch (code) {
+        case DCASGD_OK:     return "ok";
+        case DCASGD_EINVAL: return "invalid argument";
+        case DCASGD_EALIGN: return "pointer or stride not aligned";
+        case DCASGD_ESTATE: return "handle not bound/initialised";
+        case DCASGD_EHIP:   return "HIP runtime error at launch";
+        default:            return "unknown status";
+    }
+}
+
+int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming) {
+    if (!h) return DCASGD_EINVAL;
+    if (threads > 0 && !valid_threads(threads)) return fail(h, DCASGD_EINVAL);
+    if (items > 0 && !valid_items(items)) return fail(h, DCASGD_EINVAL);
+    if (max_blocks < 0) return fail(h, DCASGD_EINVAL);
+    if (threads > 0) h->threads = threads;
+    if (items > 0) h->items = items;
+    h->max_blocks = max_blocks;
+    h->streaming = streaming != 0;
+    return DCASGD_OK;
+}
+
+int dcasgd_synth_grad(const float* snap, const float* hdiag, const float* wstar, float sigma,
+                      uint64_t seed, uint32_t push_idx, void* grad_out, int as_bf16, size_t d,
+                      void* stream, int threads, int items) {
+    if (!snap || !hdiag || !wstar || !grad_out || d == 0) return DCASGD_EINVAL;
+    if (d > ((size_t)1 << 34)) return DCASGD_EINVAL;    // the counter holds i/4 in 32 bits
+    if (!std::isfinite(sigma)) return DCASGD_EINVAL;
+    if (threads <= 0) threads = 256;
+    if (items <= 0) items = 1;
+    if (!valid_threads(threads) || !valid_items(items)) return DCASGD_EINVAL;
+    if (!aligned(snap, 16) || !aligned(hdiag, 16) || !aligned(wstar, 16) ||
+        !aligned(grad_out, as_bf16 ? 8 : 16))
+        return DCASGD_EALIGN;
+    const size_t ob = d * (as_bf16 ? 2 : 4);
+    if (overlaps(grad_out, ob, snap, d * 4) || overlaps(grad_out, ob, hdiag, d * 4) ||
+        overlaps(grad_out, ob, wstar, d * 4))
+        return DCASGD_EINVAL;
+    const size_t n4 = d / 4;
+    const unsigned grid = grid_for(n4, (size_t)threads * items, 0);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    with_bool(as_bf16 != 0, [&](auto BF) {
+        with_items(items, [&](auto IT) {
+            hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, decltype(IT)::value>),
+                               dim3(grid), dim3(threads), 0, s, snap, hdiag, wstar, sigma, k0, k1,
+                               push_idx, grad_out, n4, d);
+        });
+    });
+    return hipGetLastError() == hipSuccess ? DCASGD_OK : DCASGD_EHIP;
+}
+
+}  // extern "C"

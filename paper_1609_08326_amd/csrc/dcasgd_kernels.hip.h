@@ -1,0 +1,451 @@
+// Device code of the DC-ASGD server update for gfx950 (CDNA4, wave64).
+//
+// Everything here is elementwise streaming work: each parameter is read,
+// updated and written once per push, with no reuse inside a launch.  The
+// kernels are therefore built around 128-bit global loads and stores issued
+// up front (ITEMS independent float4 groups per lane), non-temporal hints for
+// the traffic that is not touched again soon (gradients, backups), and enough
+// resident wavefronts to keep HBM busy.  There is no LDS use and no MFMA: no
+// operand is shared between lanes.
+//
+// Arithmetic contract (matches the header of the C ABI): binary32, one rounding
+// per operation, no contraction, correctly rounded sqrt and division.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#pragma clang fp contract(off)
+
+namespace dcasgd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+
+struct Hyper {
+    float eta;
+    float lambda0;
+    float ema_m;         // m of Eq. 18
+    float one_minus_m;   // 1 - m, formed once on the host in binary32
+    float eps;
+};
+
+// ---- memory helpers ---------------------------------------------------------
+template <bool NT>
+__device__ __forceinline__ f32x4 load4(const float* base, size_t quad) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(base) + quad;
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4(float* base, size_t quad, f32x4 v) {
+    f32x4* p = reinterpret_cast<f32x4*>(base) + quad;
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+__device__ __forceinline__ float widen_bf16(uint16_t h) {
+    return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+
+// binary32 -> bfloat16 bits, round to nearest, ties to even (finite inputs)
+__device__ __forceinline__ uint16_t narrow_bf16(float x) {
+    const uint32_t b = __float_as_uint(x);
+    return static_cast<uint16_t>((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+
+// Four gradient elements of group `quad`, float32 or bfloat16 in memory.
+template <bool BF16, bool NT>
+__device__ __forceinline__ f32x4 load_grad4(const void* grad, size_t quad) {
+    if constexpr (BF16) {
+        const u16x4* p = reinterpret_cast<const u16x4*>(grad) + quad;
+        u16x4 r;
+        if constexpr (NT) r = __builtin_nontemporal_load(p);
+        else r = *p;
+        f32x4 g;
+        g.x = widen_bf16(r.x); g.y = widen_bf16(r.y);
+        g.z = widen_bf16(r.z); g.w = widen_bf16(r.w);
+        return g;
+    } else {
+        return load4<NT>(reinterpret_cast<const float*>(grad), quad);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_grad1(const void* grad, size_t i) {
+    if constexpr (BF16) return widen_bf16(reinterpret_cast<const uint16_t*>(grad)[i]);
+    else return reinterpret_cast<const float*>(grad)[i];
+}
+
+// ---- the update rule ----------------------------------------------------------
+// Eq. 4.1 applied to one parameter; in the adaptive variant Eq. 18 refreshes
+// MeanSquare first and lambda is lambda0 / sqrt(MeanSquare + eps).
+template <bool ADAPTIVE>
+__device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
+                                           float& w, float& ms) {
+    const float gsq = g * g;
+    float lam = hp.lambda0;
+    if constexpr (ADAPTIVE) {
+        const float keep = hp.ema_m * ms;
+        const float add = hp.one_minus_m * gsq;
+        ms = keep + add;
+        const float under = ms + hp.eps;
+        const float root = __builtin_sqrtf(under);
+        lam = hp.lambda0 / root;
+    }
+    const float drift = w - b;            // how far the model moved since the pull
+    const float curv = lam * gsq;         // diagonal Hessian estimate
+    const float comp = curv * drift;
+    const float gdc = g + comp;           // delay-compensated gradient
+    const float step = hp.eta * gdc;
+    w = w - step;
+}
+
+template <bool ADAPTIVE>
+__device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, const f32x4& b,
+                                            f32x4& w, f32x4& ms) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float wc = w[c], mc = ms[c];
+        apply_push<ADAPTIVE>(hp, g[c], b[c], wc, mc);
+        w[c] = wc;
+        ms[c] = mc;
+    }
+}
+
+// ---- push (optionally fused with the pusher's pull) ----------------------------
+// Work is cut into tiles of blockDim.x * ITEMS float4 groups; lane l of a tile
+// touches groups l, l + blockDim.x, ... so every wave-wide access is one
+// contiguous 1 KiB run.  Blocks walk tiles with stride gridDim.x.
+template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, bool NT, bool CHECKED>
+__device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w,
+                                          float* __restrict__ ms, float* __restrict__ bak,
+                                          const void* __restrict__ grad, size_t first,
+                                          size_t n4) {
+    f32x4 W[ITEMS], B[ITEMS], G[ITEMS], S[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const size_t q = first + (size_t)j * blockDim.x;
+        if (!CHECKED || q < n4) {
+            G[j] = load_grad4<BF16, NT>(grad, q);
+            B[j] = load4<NT>(bak, q);
+            W[j] = load4<false>(w, q);
+            if constexpr (ADAPTIVE) S[j] = load4<false>(ms, q);
+            else S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        } else {
+            G[j] = B[j] = W[j] = S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const size_t q = first + (size_t)j * blockDim.x;
+        apply_push4<ADAPTIVE>(hp, G[j], B[j], W[j], S[j]);
+        if (!CHECKED || q < n4) {
+            store4<false>(w, q, W[j]);
+            if constexpr (ADAPTIVE) store4<false>(ms, q, S[j]);
+            if constexpr (PULL) store4<NT>(bak, q, W[j]);
+        }
+    }
+}
+
+template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, bool NT>
+__global__ void __launch_bounds__(512)
+push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __restrict__ bak,
+            const void* __restrict__ grad, size_t n4, size_t d) {
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t first = tile * tile_quads + threadIdx.x;
+        if ((tile + 1) * tile_quads <= n4)
+            push_tile<ADAPTIVE, BF16, PULL, ITEMS, NT, false>(hp, w, ms, bak, grad, first, n4);
+        else
+            push_tile<ADAPTIVE, BF16, PULL, ITEMS, NT, true>(hp, w, ms, bak, grad, first, n4);
+    }
+    // up to three parameters beyond the last full group of four
+    if (blockIdx.x == 0) {
+        const size_t i = 4 * n4 + threadIdx.x;
+        if (i < d) {
+            float wi = w[i];
+            float si = 0.f;
+            if constexpr (ADAPTIVE) si = ms[i];
+            apply_push<ADAPTIVE>(hp, load_grad1<BF16>(grad, i), bak[i], wi, si);
+            w[i] = wi;
+            if constexpr (ADAPTIVE) ms[i] = si;
+            if constexpr (PULL) bak[i] = wi;
+        }
+    }
+}
+
+// ---- K queued pushes in one pass (push; pull; push; pull; ...) -------------------
+struct BatchArgs {
+    const void* grad[16];   // grad[k]: gradient of queue entry k
+    float* bak[16];         // bak[k]: backup row of the worker of entry k (all distinct)
+    int K;
+};
+
+// w and ms stay in registers across the queue; entry k reads its gradient and
+// its worker's backup, updates, and overwrites that backup with the new w.
+// Entries are handled KC at a time so that 2*KC 128-bit loads are in flight.
+template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool CHECKED>
+__device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ w,
+                                           float* __restrict__ ms, const BatchArgs& a,
+                                           size_t q, size_t n4) {
+    if (CHECKED && q >= n4) return;
+    f32x4 W = load4<false>(w, q);
+    f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (ADAPTIVE) S = load4<false>(ms, q);
+    int k0 = 0;
+    for (; k0 + KC <= a.K; k0 += KC) {
+        f32x4 G[KC], B[KC];
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk) {
+            G[kk] = load_grad4<BF16, NT>(a.grad[k0 + kk], q);
+            B[kk] = load4<NT>(a.bak[k0 + kk], q);
+        }
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk) {
+            apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S);
+            store4<NT>(a.bak[k0 + kk], q, W);
+        }
+    }
+    for (; k0 < a.K; ++k0) {
+        const f32x4 G = load_grad4<BF16, NT>(a.grad[k0], q);
+        const f32x4 B = load4<NT>(a.bak[k0], q);
+        apply_push4<ADAPTIVE>(hp, G, B, W, S);
+        store4<NT>(a.bak[k0], q, W);
+    }
+    store4<false>(w, q, W);
+    if constexpr (ADAPTIVE) store4<false>(ms, q, S);
+}
+
+template <bool ADAPTIVE, bool BF16, int KC, bool NT>
+__global__ void __launch_bounds__(256)
+push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, BatchArgs a,
+                  size_t n4, size_t d) {
+    const size_t ntiles = (n4 + blockDim.x - 1) / blockDim.x;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t q = tile * blockDim.x + threadIdx.x;
+        if ((tile + 1) * blockDim.x <= n4)
+            batch_quad<ADAPTIVE, BF16, KC, NT, false>(hp, w, ms, a, q, n4);
+        else
+            batch_quad<ADAPTIVE, BF16, KC, NT, true>(hp, w, ms, a, q, n4);
+    }
+    if (blockIdx.x == 0) {
+        const size_t i = 4 * n4 + threadIdx.x;
+        if (i < d) {
+            float wi = w[i];
+            float si = 0.f;
+            if constexpr (ADAPTIVE) si = ms[i];
+            for (int k = 0; k < a.K; ++k) {
+                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[k], i), a.bak[k][i], wi, si);
+                a.bak[k][i] = wi;
+            }
+            w[i] = wi;
+            if constexpr (ADAPTIVE) ms[i] = si;
+        }
+    }
+}
+
+// ---- pull: w_bak(m) <- w ---------------------------------------------------------
+template <int ITEMS, bool NT>
+__global__ void __launch_bounds__(512)
+pull_kernel(const float* __restrict__ w, float* __restrict__ bak, size_t n4, size_t d) {
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t first = tile * tile_quads + threadIdx.x;
+        f32x4 V[ITEMS];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const size_t q = first + (size_t)j * blockDim.x;
+            if (q < n4) V[j] = load4<false>(w, q);
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const size_t q = first + (size_t)j * blockDim.x;
+            if (q < n4) store4<NT>(bak, q, V[j]);
+        }
+    }
+    if (blockIdx.x == 0) {
+        const size_t i = 4 * n4 + threadIdx.x;
+        if (i < d) bak[i] = w[i];
+    }
+}
+
+// ---- fill (MeanSquare <- 0 at initialisation) -----------------------------------
+__global__ void __launch_bounds__(512)
+fill_kernel(float* __restrict__ dst, float value, size_t n4, size_t d) {
+    const f32x4 v = f32x4{value, value, value, value};
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < n4;
+         q += (size_t)gridDim.x * blockDim.x)
+        store4<false>(dst, q, v);
+    if (blockIdx.x == 0) {
+        const size_t i = 4 * n4 + threadIdx.x;
+        if (i < d) dst[i] = value;
+    }
+}
+
+// ---- synthetic worker: counter-based noise ------------------------------------
+// Philox4x32 with ten rounds (Salmon et al., SC'11): each round multiplies
+// words 0 and 2 by fixed odd constants, mixes the high halves with the other
+// two words and the round key, and the key advances by a Weyl step.
+struct Words4 { uint32_t a, b, c, d; };
+
+__device__ __forceinline__ Words4 philox10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                           uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p02 = (uint64_t)c0 * 0xD2511F53ull;
+        const uint64_t p20 = (uint64_t)c2 * 0xCD9E8D57ull;
+        const uint32_t y0 = (uint32_t)(p20 >> 32) ^ c1 ^ k0;
+        const uint32_t y2 = (uint32_t)(p02 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p20;
+        c3 = (uint32_t)p02;
+        c0 = y0;
+        c2 = y2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Words4{c0, c1, c2, c3};
+}
+
+// sqrt(-2 ln u) for u = ((word >> 8) + 1) / 2^24, with ln through the atanh
+// series on the mantissa folded into (sqrt(1/2), sqrt(2)].
+__device__ __forceinline__ float radius_from_word(uint32_t word) {
+    const float u = (float)((word >> 8) + 1u) * 0x1p-24f;
+    const uint32_t ub = __float_as_uint(u);
+    int ex = (int)(ub >> 23) - 127;
+    float mant = __uint_as_float((ub & 0x007FFFFFu) | 0x3F800000u);
+    const bool fold = mant > 1.41421354f;
+    const float halved = mant * 0.5f;
+    mant = fold ? halved : mant;
+    ex = fold ? ex + 1 : ex;
+    const float num = mant - 1.0f;
+    const float den = mant + 1.0f;
+    const float s = num / den;
+    const float ss = s * s;
+    float acc = 0.11111111f;
+    acc = acc * ss; acc = acc + 0.14285715f;
+    acc = acc * ss; acc = acc + 0.2f;
+    acc = acc * ss; acc = acc + 0.33333334f;
+    acc = acc * ss; acc = acc + 1.0f;
+    const float s2x = 2.0f * s;
+    const float lnm = s2x * acc;
+    const float lne = (float)ex * 0.69314718f;
+    const float lnu = lne + lnm;
+    const float arg = -2.0f * lnu;
+    return __builtin_sqrtf(arg);
+}
+
+// (cos, sin) of 2*pi*j/2^24, j = word >> 8: fold to [0, pi/4], Taylor
+// polynomials, then undo the fold by octant.
+__device__ __forceinline__ void circle_from_word(uint32_t word, float& co, float& si) {
+    const uint32_t j = word >> 8;
+    const uint32_t quad = j >> 22;
+    const uint32_t frac = j & 0x3FFFFFu;
+    const bool mirror = frac > 0x200000u;
+    const uint32_t folded = mirror ? 0x400000u - frac : frac;
+    const float x = (float)folded * 0x1.921fb6p-22f;
+    const float xx = x * x;
+    float ps = 2.7557319e-6f;
+    ps = ps * xx; ps = ps - 1.9841270e-4f;
+    ps = ps * xx; ps = ps + 8.3333333e-3f;
+    ps = ps * xx; ps = ps - 0.16666667f;
+    ps = ps * xx; ps = ps + 1.0f;
+    const float sin_x = x * ps;
+    float pc = -2.7557319e-7f;
+    pc = pc * xx; pc = pc + 2.4801587e-5f;
+    pc = pc * xx; pc = pc - 1.3888889e-3f;
+    pc = pc * xx; pc = pc + 4.1666668e-2f;
+    pc = pc * xx; pc = pc - 0.5f;
+    pc = pc * xx;
+    const float cos_x = pc + 1.0f;
+    const float sa = mirror ? cos_x : sin_x;   // sine of the first-quadrant angle
+    const float ca = mirror ? sin_x : cos_x;
+    // rotate by quad * 90 degrees
+    const float c_even = (quad & 2u) ? -ca : ca;
+    const float s_even = (quad & 2u) ? -sa : sa;
+    const float c_odd = (quad & 2u) ? sa : -sa;
+    const float s_odd = (quad & 2u) ? -ca : ca;
+    co = (quad & 1u) ? c_odd : c_even;
+    si = (quad & 1u) ? s_odd : s_even;
+}
+
+__device__ __forceinline__ f32x4 normals_for_quad(uint32_t k0, uint32_t k1, uint32_t t,
+                                                  uint32_t quad_index) {
+    const Words4 x = philox10(quad_index, t, 0u, 0u, k0, k1);
+    float c, s;
+    f32x4 z;
+    const float r0 = radius_from_word(x.a);
+    circle_from_word(x.b, c, s);
+    z.x = r0 * c; z.y = r0 * s;
+    const float r1 = radius_from_word(x.c);
+    circle_from_word(x.d, c, s);
+    z.z = r1 * c; z.w = r1 * s;
+    return z;
+}
+
+__device__ __forceinline__ float synth_one(float snap, float h, float wstar, float sigma, float z) {
+    const float off = snap - wstar;
+    const float pull_back = h * off;
+    const float noise = sigma * z;
+    return pull_back + noise;
+}
+
+// g = h * (snap - wstar) + sigma * z, four parameters per Philox counter.
+template <bool BF16, int ITEMS>
+__global__ void __launch_bounds__(512)
+synth_grad_kernel(const float* __restrict__ snap, const float* __restrict__ hdiag,
+                  const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
+                  uint32_t t, void* __restrict__ out, size_t n4, size_t d) {
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t first = tile * tile_quads + threadIdx.x;
+        f32x4 A[ITEMS], H[ITEMS], O[ITEMS];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const size_t q = first + (size_t)j * blockDim.x;
+            if (q < n4) {
+                A[j] = load4<true>(snap, q);
+                H[j] = load4<false>(hdiag, q);
+                O[j] = load4<false>(wstar, q);
+            } else {
+                A[j] = H[j] = O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const size_t q = first + (size_t)j * blockDim.x;
+            if (q < n4) {
+                const f32x4 z = normals_for_quad(k0, k1, t, (uint32_t)q);
+                f32x4 g;
+                g.x = synth_one(A[j].x, H[j].x, O[j].x, sigma, z.x);
+                g.y = synth_one(A[j].y, H[j].y, O[j].y, sigma, z.y);
+                g.z = synth_one(A[j].z, H[j].z, O[j].z, sigma, z.z);
+                g.w = synth_one(A[j].w, H[j].w, O[j].w, sigma, z.w);
+                if constexpr (BF16) {
+                    u16x4 pk;
+                    pk.x = narrow_bf16(g.x); pk.y = narrow_bf16(g.y);
+                    pk.z = narrow_bf16(g.z); pk.w = narrow_bf16(g.w);
+                    reinterpret_cast<u16x4*>(out)[q] = pk;
+                } else {
+                    store4<false>(reinterpret_cast<float*>(out), q, g);
+                }
+            }
+        }
+    }
+    // ragged tail: the last, partial group of four shares one counter
+    if (blockIdx.x == 0 && threadIdx.x == 0 && 4 * n4 < d) {
+        const f32x4 z = normals_for_quad(k0, k1, t, (uint32_t)n4);
+        const float zz[4] = {z.x, z.y, z.z, z.w};
+        for (size_t i = 4 * n4; i < d; ++i) {
+            const float g = synth_one(snap[i], hdiag[i], wstar[i], sigma, zz[i - 4 * n4]);
+            if constexpr (BF16) reinterpret_cast<uint16_t*>(out)[i] = narrow_bf16(g);
+            else reinterpret_cast<float*>(out)[i] = g;
+        }
+    }
+}
+
+}  // namespace dcasgd

@@ -1,0 +1,90 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_1609_08326_amd import binding, build
+    if build.is_stale():
+        build.build_library(force=True)
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dcasgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dcasgd_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    from paper_1609_08326_amd import binding
+    names = declared_symbols()
+    assert "dcasgd_create" in names and "dcasgd_push_batch" in names and len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding._PROTOTYPES) == names
+
+
+def test_create_validates_without_touching_a_gpu(lib):
+    from paper_1609_08326_amd import binding as B
+    ok = lib.dcasgd_create(100, 4, 0.1, 2.0, B.MODE_A | B.PULL_ON_PUSH, 0.95, 1e-7)
+    assert ok
+    assert lib.dcasgd_step(ok) == 0
+    # not bound yet: every state-changing call is refused
+    assert lib.dcasgd_init(ok, None) == B.ESTATE
+    assert lib.dcasgd_push(ok, 0, None, None) == B.ESTATE
+    assert not lib.dcasgd_pull(ok, 0)
+    assert lib.dcasgd_last_error(ok) == B.ESTATE
+    assert lib.dcasgd_bind(ok, None, None, 100, None) == B.EINVAL
+    assert lib.dcasgd_bind(ok, 16, 4096, 96, 8192) == B.EINVAL        # stride < d
+    assert lib.dcasgd_bind(ok, 20, 4096, 100, 8192) == B.EALIGN       # w not 16-byte aligned
+    assert lib.dcasgd_bind(ok, 16, 4096, 102, 8192) == B.EALIGN       # stride not a multiple of 4
+    assert lib.dcasgd_bind(ok, 4096, 4096, 100, 81920) == B.EINVAL    # w overlaps bak
+    assert lib.dcasgd_set_launch(ok, 100, 0, 0, 1) == B.EINVAL
+    assert lib.dcasgd_set_launch(ok, 1024, 0, 0, 1) == B.EINVAL
+    assert lib.dcasgd_set_launch(ok, 256, 3, 0, 1) == B.EINVAL
+    assert lib.dcasgd_set_launch(ok, 256, 4, -1, 1) == B.EINVAL
+    assert lib.dcasgd_set_launch(ok, 256, 4, 0, 1) == B.OK
+    assert lib.dcasgd_destroy(ok) == B.OK
+    for bad in [(0, 4, 0.1, 2.0, B.MODE_A, 0.9, 1e-7), (10, 0, 0.1, 2.0, B.MODE_A, 0.9, 1e-7),
+                (10, 4, 0.1, 2.0, 7, 0.9, 1e-7), (10, 4, 0.1, 2.0, B.MODE_A, 1.0, 1e-7),
+                (10, 4, 0.1, 2.0, B.MODE_A, -0.1, 1e-7), (10, 4, float("nan"), 2.0, B.MODE_C, 0, 0),
+                (10, 4, 0.1, 2.0, B.MODE_A, 0.9, -1.0), (10, 4, 0.1, 2.0, B.MODE_A | (1 << 8), 0.9, 0)]:
+        assert not lib.dcasgd_create(*bad), bad
+    assert lib.dcasgd_destroy(None) == B.EINVAL
+    assert lib.dcasgd_strerror(B.EALIGN).decode().startswith("pointer")
+
+
+def test_synth_grad_validates_without_touching_a_gpu(lib):
+    from paper_1609_08326_amd import binding as B
+    assert lib.dcasgd_synth_grad(None, 16, 32, 0.1, 1, 0, 48, 0, 4, None, 0, 0) == B.EINVAL
+    assert lib.dcasgd_synth_grad(16, 4096, 8192, 0.1, 1, 0, 12288, 0, 0, None, 0, 0) == B.EINVAL
+    assert lib.dcasgd_synth_grad(20, 4096, 8192, 0.1, 1, 0, 12288, 0, 8, None, 0, 0) == B.EALIGN
+    assert lib.dcasgd_synth_grad(16, 4096, 8192, 0.1, 1, 0, 16, 0, 8, None, 0, 0) == B.EINVAL
+    assert lib.dcasgd_synth_grad(16, 4096, 8192, 0.1, 1, 0, 12288, 0, 8, None, 96, 1) == B.EINVAL
+
+
+def test_workloads_are_deterministic_and_shaped():
+    from paper_1609_08326_amd import workloads as W
+    assert [c.d for c in W.CONFIGS] == [272474, 272474, 25557032, 25557032, 138357544]
+    assert [c.M for c in W.CONFIGS] == [4, 8, 16, 16, 32]
+    assert [c.T for c in W.CONFIGS] == [2000, 4000, 200, 320, 64]
+    c0 = W.CONFIGS[0]
+    assert list(c0.arrivals()[:6]) == [0, 1, 2, 3, 0, 1]
+    c1 = W.CONFIGS[1]
+    a, b = c1.arrivals(), c1.arrivals()
+    assert (a == b).all() and a.min() == 0 and a.max() == c1.M - 1
+    h = c1.hdiag()
+    assert h.dtype.name == "float32" and h.min() >= 1e-3 * 0.999 and h.max() <= 1.0
+    assert abs(float(c1.wstar().std()) - 1.0) < 0.01
+    c3 = W.CONFIGS[3].replace(d=16)
+    q = c3.arrivals().reshape(-1, 16)
+    assert all(sorted(r) == list(range(16)) for r in q.tolist())
+    idx = W.CONFIGS[2].sample_indices(1000, edge=64)
+    assert idx[0] == 0 and idx[-1] == W.CONFIGS[2].d - 1 and (idx[1:] > idx[:-1]).all()

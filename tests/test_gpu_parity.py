@@ -1,0 +1,168 @@
+"""GPU parity: the HIP library against the CPU oracle, bit for bit, on the same
+seeded inputs.  Tolerance: none - the paper's update (Eq. 4.1, Eq. 18) is
+evaluated in the same binary32 operation order on both sides, with fused
+multiply-add off and correctly rounded sqrt/division, so every word of w,
+MeanSquare and all backups must be identical."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1609_08326_amd import workloads as W
+
+from gpu_harness import GpuRun, assert_same_bits, compare, oracle_run
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def small(d, M=3, T=24, mode=W.MODE_A, bf16=False, order="iid", K=1, seed=77):
+    return W.Workload("small", d=d, M=M, T=T, mode=mode, eta=0.1,
+                      lambda0=2.0 if mode == W.MODE_A else 0.04, ema_m=0.95, eps=1e-7,
+                      h_lo=1e-3, h_hi=1.0, wstar_sigma=1.0, sigma=0.01, order=order, K=K,
+                      grad_bf16=bf16, seed=seed)
+
+
+def test_synth_grad_matches_oracle():
+    import torch
+    from paper_1609_08326_amd import binding as B
+    rng = np.random.default_rng(0)
+    for d in (1, 2, 3, 4, 5, 7, 1024, 4097, 100003):
+        snap = rng.standard_normal(d).astype(np.float32)
+        h = rng.uniform(1e-3, 1, d).astype(np.float32)
+        ws = rng.standard_normal(d).astype(np.float32)
+        for bf16 in (False, True):
+            for (threads, items) in ((0, 0), (64, 4), (512, 2)):
+                say("synth_grad d=%d bf16=%s launch=%s" % (d, bf16, (threads, items)))
+                out = torch.empty(d, dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+                B.synth_grad(torch.from_numpy(snap).cuda(), torch.from_numpy(h).cuda(),
+                             torch.from_numpy(ws).cuda(), 0.01, 0xDEADBEEF12345, 9, out,
+                             threads=threads, items=items)
+                got = out.float().cpu().numpy()
+                ref = oracle.synth_grad(snap, h, ws, 0.01, 0xDEADBEEF12345, 9, as_bf16=bf16)
+                assert_same_bits(got, ref, "synth_grad d=%d bf16=%s" % (d, bf16))
+
+
+@pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("fused", [True, False])
+def test_small_sizes_every_tail(mode, bf16, fused):
+    """Sizes around tile and vector boundaries, several launch shapes."""
+    for d in (1, 3, 4, 5, 255, 256, 1023, 1025, 2048 + 3, 40000 + 1):
+        for launch in (None, dict(threads=64, items=1), dict(threads=128, items=4),
+                       dict(threads=512, items=2, max_blocks=3),
+                       dict(threads=256, items=2, streaming=False)):
+            wl = small(d, mode=mode, bf16=bf16)
+            say("small d=%d mode=%d bf16=%s fused=%s launch=%s" % (d, mode, bf16, fused, launch))
+            run = GpuRun(wl, fused=fused, launch=launch)
+            ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1)
+            compare(run, ref, tag="d=%d" % d)
+
+
+@pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_push_batch_equals_unbatched_and_oracle(mode, bf16):
+    for d in (3, 257, 4096 + 2, 70001):
+        for K in (1, 2, 5, 8, 16):
+            wl = small(d, M=16, T=3 * K, mode=mode, bf16=bf16, order="queues", K=K)
+            say("batch d=%d K=%d mode=%d bf16=%s" % (d, K, mode, bf16))
+            run = GpuRun(wl, batched=True, launch=dict(threads=128, items=1))
+            ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1)
+            compare(run, ref, tag="batched d=%d K=%d" % (d, K))
+            plain = GpuRun(wl, batched=False)
+            assert_same_bits(run.w, plain.w, "batched vs unbatched w")
+
+
+def test_push_batch_with_repeated_workers():
+    """A queue that names a worker twice is split at the repeat."""
+    wl = small(5003, M=4, T=32, order="iid", K=8, seed=5)
+    say("batch with repeats")
+    run = GpuRun(wl, batched=True)
+    assert any(len(set(run.arrivals[i:i + 8])) < 8 for i in range(0, 32, 8))
+    ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1)
+    compare(run, ref, tag="repeats")
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_config_full_elementwise(cfg):
+    """Configurations 0 and 1 (ResNet-20-sized): every element, every push."""
+    wl = W.CONFIGS[cfg]
+    say("full config %s" % wl.name)
+    run = GpuRun(wl)
+    ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=16)
+    compare(run, ref, tag=wl.name)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_config_full_size_sampled(cfg):
+    """Configurations 2-4 at full size, in the launch shape bench.py times;
+    the oracle follows a seeded sample of elements (both ends of the vector
+    included) through every push - elements never interact, so each sampled
+    element's history is complete."""
+    wl = W.CONFIGS[cfg]
+    say("full-size sampled config %s" % wl.name)
+    run = GpuRun(wl, batched=(wl.K > 1))
+    idx = wl.sample_indices(150_000, edge=4096)
+    ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, idx=idx, nthreads=16)
+    compare(run, ref, idx=idx, tag=wl.name)
+    # any-size properties: each backup equals w as of its worker's last pull
+    last = int(run.arrivals[-1])
+    assert_same_bits(run.bak[last], run.w, "last puller's backup is w")
+    never = [m for m in range(wl.M) if m not in set(run.arrivals.tolist())]
+    for m in never:
+        assert_same_bits(run.bak[m], wl.w0(), "untouched backup is w0")
+    assert np.all(np.isfinite(run.w))
+
+
+def test_pull_semantics_and_bookkeeping():
+    import torch
+    from paper_1609_08326_amd import binding as B
+    d, M = 10007, 3
+    rng = np.random.default_rng(3)
+    w0 = torch.from_numpy(rng.standard_normal(d).astype(np.float32)).cuda()
+    w0_host = w0.cpu().numpy()
+    sv = B.Server(w0, M, 0.1, 0.04, B.MODE_C)
+    g = torch.from_numpy(rng.standard_normal(d).astype(np.float32)).cuda()
+    for m in range(M):
+        assert_same_bits(sv.pull(m).cpu().numpy(), w0_host, "initial backup")
+    sv.push(1, g)
+    torch.cuda.synchronize()
+    assert sv.t == 1
+    w1 = sv.w.cpu().numpy()
+    assert_same_bits(sv.snapshot(1).cpu().numpy(), w0_host, "push alone leaves the backup")
+    assert_same_bits(sv.pull(1).cpu().numpy(), w1, "pull copies w")
+    assert_same_bits(sv.snapshot(0).cpu().numpy(), w0_host, "other backups untouched")
+    ref = oracle.Server(w0_host, M, 0.1, 0.04, oracle.MODE_C)
+    ref.push(1, g.cpu().numpy())
+    assert_same_bits(w1, ref.w(), "single push")
+
+
+def test_rejected_calls_launch_nothing():
+    import ctypes as C
+    import torch
+    from paper_1609_08326_amd import binding as B
+    lib = B.load()
+    d, M = 4096, 2
+    w0 = torch.zeros(d, device="cuda")
+    sv = B.Server(w0, M, 0.1, 2.0, B.MODE_A, 0.9, 1e-7)
+    g = torch.ones(d + 8, device="cuda")
+    s = int(torch.cuda.current_stream().cuda_stream)
+    assert lib.dcasgd_push(sv._h, M, g.data_ptr(), s) == B.EINVAL
+    assert lib.dcasgd_push(sv._h, -1, g.data_ptr(), s) == B.EINVAL
+    assert lib.dcasgd_push(sv._h, 0, None, s) == B.EINVAL
+    assert lib.dcasgd_push(sv._h, 0, g.data_ptr() + 4, s) == B.EALIGN
+    assert lib.dcasgd_push(sv._h, 0, sv.w.data_ptr(), s) == B.EINVAL          # overlap
+    wa = (C.c_int * 17)(*([0] * 17))
+    ga = (C.c_void_p * 17)(*([g.data_ptr()] * 17))
+    assert lib.dcasgd_push_batch(sv._h, wa, ga, 0, s) == B.EINVAL
+    assert lib.dcasgd_push_batch(sv._h, wa, ga, 17, s) == B.EINVAL
+    assert not lib.dcasgd_pull(sv._h, M)
+    assert lib.dcasgd_last_error(sv._h) == B.EINVAL
+    torch.cuda.synchronize()
+    assert sv.t == 0
+    assert float(sv.w.abs().max()) == 0.0
