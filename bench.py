@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the DC-ASGD server hot path on one MI355X.
+
+A step is one worker arrival at the parameter server, all of it in HIP
+kernels on torch's current stream:
+    synthetic worker gradient at the worker's backup  ->  delay-compensated
+    push (Eq. 4.1 / Eq. 18) fused with the worker's pull (backup refresh).
+For the queued workload a step is one dcasgd_push_batch call over K arrivals
+(K gradient launches + one fused launch); element-updates are counted per
+arrival either way.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is whole-path element-updates/s; `roofline`
+describes the server-update kernel alone (HIP events around it, inside the
+timed region); `cpu_baseline` times the CPU oracle on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes_per_update(wl) -> float:
+    """Bytes the method itself must move per element per applied push
+    (fused push+pull): reads w, backup, gradient (+MeanSquare), writes w,
+    backup (+MeanSquare).  Queue of K: w/MeanSquare once per queue."""
+    g = 2 if wl.grad_bf16 else 4
+    adaptive = wl.mode == 1
+    if wl.K > 1:
+        per_queue = (16 if adaptive else 8) + wl.K * (g + 4 + 4)
+        return per_queue / wl.K
+    return (4 + 4 + g + 4 + 4) + (8 if adaptive else 0)
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch from the committed counter summary, if any."""
+    path = os.path.join(ROOT, "profiles", "pmc_%s.txt" % name)
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(wl, target_s: float):
+    """Time the oracle (as it stands) on a bounded sample of the workload."""
+    import numpy as np
+    import oracle
+    cores = min(16, len(os.sched_getaffinity(0)))
+    n = min(wl.d, 8 << 20)
+    hd = wl.hdiag()[:n]
+    ws = wl.wstar()[:n]
+    order = wl.arrivals()
+
+    def timed(T):
+        sv = oracle.Server(np.zeros(n, dtype=np.float32), wl.M, wl.eta, wl.lambda0, wl.mode,
+                           wl.ema_m, wl.eps)
+        t0 = time.perf_counter()
+        sv.run(order[:T], hd, ws, wl.sigma, wl.seed, as_bf16=wl.grad_bf16, nthreads=cores)
+        return time.perf_counter() - t0
+
+    probe = max(2, min(8, wl.T))
+    dt = timed(probe)
+    T = int(max(probe, min(wl.T, target_s / max(dt / probe, 1e-9))))
+    dt = timed(T)
+    return {"value": n * T / dt, "unit": "element-updates/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d of %d elements, first %d of %d arrivals, gradient+push+pull, "
+                      "%d threads over element chunks, %.1f s" % (n, wl.d, T, wl.T, cores, dt)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--threads", type=int, default=0)
+    ap.add_argument("--items", type=int, default=0)
+    ap.add_argument("--max-blocks", type=int, default=0)
+    ap.add_argument("--no-streaming", action="store_true")
+    ap.add_argument("--synth-threads", type=int, default=0)
+    ap.add_argument("--synth-items", type=int, default=0)
+    ap.add_argument("--no-events", action="store_true",
+                    help="skip per-kernel events (whole-path timing only)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="CPU oracle sample length; 0 skips the baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by index range, "
+              "see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1609_08326_amd import binding as B
+    from paper_1609_08326_amd import workloads as W
+
+    wl = W.get(args.workload)
+    batched = wl.K > 1
+    K = wl.K
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n_steps, n_warm = args.steps, args.warmup
+    arrivals = wl.replace(T=(n_steps + n_warm) * K).arrivals()
+
+    hd = torch.from_numpy(wl.hdiag()).to(dev)
+    ws = torch.from_numpy(wl.wstar()).to(dev)
+    w = torch.from_numpy(wl.w0()).to(dev)
+    sv = B.Server(w, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps,
+                  grad_bf16=wl.grad_bf16, pull_on_push=not batched)
+    if args.threads or args.items or args.max_blocks or args.no_streaming:
+        sv.set_launch(args.threads, args.items, args.max_blocks, not args.no_streaming)
+    gdt = torch.bfloat16 if wl.grad_bf16 else torch.float32
+    gbuf = [torch.empty(wl.d, dtype=gdt, device=dev) for _ in range(K)]
+
+    use_events = not args.no_events
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_steps)] \
+        if use_events else None
+
+    def step(i: int, rec) -> None:
+        base = i * K
+        ms_ = [int(m) for m in arrivals[base:base + K]]
+        if rec:
+            rec[0].record()
+        for j, m in enumerate(ms_):
+            B.synth_grad(sv.snapshot(m), hd, ws, wl.sigma, wl.seed, base + j, gbuf[j],
+                         threads=args.synth_threads, items=args.synth_items)
+        if rec:
+            rec[1].record()
+        if batched:
+            sv.push_batch(ms_, gbuf)
+        else:
+            sv.push(ms_[0], gbuf[0])
+        if rec:
+            rec[2].record()
+
+    for i in range(n_warm):
+        step(i, None)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_steps):
+        step(n_warm + i, ev[i] if use_events else None)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    updates = wl.d * K * n_steps
+    value = updates / elapsed
+    bpu = algorithmic_bytes_per_update(wl)
+    kname = "push_batch_K%d" % K if batched else "push_fused"
+    out = {
+        "metric": "element-updates/sec",
+        "value": value,
+        "unit": "element-updates/s",
+        "n_gpus": 1,
+        "steps": n_steps,
+        "warmup": n_warm,
+        "ms_per_step": 1e3 * elapsed / n_steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if not wl.grad_bf16 else "f32 (bf16 gradients)",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "d": wl.d, "M": wl.M, "K": K,
+                   "variant": "DC-ASGD-a" if wl.mode == 1 else "DC-ASGD-c",
+                   "step": "synth_grad x%d + fused push+pull" % K},
+    }
+    if use_events:
+        synth_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / n_steps
+        push_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / n_steps
+        launch_bytes = bpu * wl.d * K
+        achieved = launch_bytes / (push_ms * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": achieved,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": read_traffic("%s_%s" % (kname, wl.name.split("_")[0])),
+                           "avg_launch_ms": push_ms,
+                           "algorithmic_bytes_per_launch": launch_bytes,
+                           "bytes_per_element_update": bpu}
+        out["server_update_only"] = {"value": wl.d * K / (push_ms * 1e-3),
+                                     "unit": "element-updates/s"}
+        synth_bytes = (12 + (2 if wl.grad_bf16 else 4)) * wl.d * K
+        out["worker_kernel"] = {"kernel": "synth_grad", "avg_ms_per_step": synth_ms,
+                                "achieved_GBs": synth_bytes / (synth_ms * 1e-3) / 1e9}
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
