@@ -52,29 +52,32 @@ def read_traffic(name: str):
 
 
 def cpu_baseline(wl, target_s: float):
-    """Time the oracle (as it stands) on a bounded sample of the workload."""
+    """Time the oracle (as it stands) on a bounded sample of the workload:
+    a leading slice of the parameter vector, the workload's arrival order
+    (continued with the same generator if the sample needs more arrivals)."""
     import numpy as np
     import oracle
     cores = min(16, len(os.sched_getaffinity(0)))
-    n = min(wl.d, 8 << 20)
+    n = min(wl.d, 32 << 20)
     hd = wl.hdiag()[:n]
     ws = wl.wstar()[:n]
-    order = wl.arrivals()
 
     def timed(T):
+        order = wl.replace(T=-(-T // wl.K) * wl.K).arrivals()[:T]
         sv = oracle.Server(np.zeros(n, dtype=np.float32), wl.M, wl.eta, wl.lambda0, wl.mode,
                            wl.ema_m, wl.eps)
         t0 = time.perf_counter()
-        sv.run(order[:T], hd, ws, wl.sigma, wl.seed, as_bf16=wl.grad_bf16, nthreads=cores)
+        sv.run(order, hd, ws, wl.sigma, wl.seed, as_bf16=wl.grad_bf16, nthreads=cores)
         return time.perf_counter() - t0
 
-    probe = max(2, min(8, wl.T))
+    probe = 8
     dt = timed(probe)
-    T = int(max(probe, min(wl.T, target_s / max(dt / probe, 1e-9))))
+    T = int(max(probe, min(20000, target_s / max(dt / probe, 1e-9))))
     dt = timed(T)
     return {"value": n * T / dt, "unit": "element-updates/s", "cores": cores, "kind": "oracle",
-            "sample": "first %d of %d elements, first %d of %d arrivals, gradient+push+pull, "
-                      "%d threads over element chunks, %.1f s" % (n, wl.d, T, wl.T, cores, dt)}
+            "sample": "first %d of %d elements, %d arrivals in the workload's order, "
+                      "gradient+push+pull per arrival, %d threads over element chunks, %.1f s"
+                      % (n, wl.d, T, cores, dt)}
 
 
 def main() -> int:
@@ -86,7 +89,7 @@ def main() -> int:
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--items", type=int, default=0)
     ap.add_argument("--max-blocks", type=int, default=0)
-    ap.add_argument("--no-streaming", action="store_true")
+    ap.add_argument("--streaming", type=int, default=-1, help="0, 1 or 2 (see dcasgd_set_launch)")
     ap.add_argument("--synth-threads", type=int, default=0)
     ap.add_argument("--synth-items", type=int, default=0)
     ap.add_argument("--no-events", action="store_true",
@@ -116,8 +119,9 @@ def main() -> int:
     w = torch.from_numpy(wl.w0()).to(dev)
     sv = B.Server(w, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps,
                   grad_bf16=wl.grad_bf16, pull_on_push=not batched)
-    if args.threads or args.items or args.max_blocks or args.no_streaming:
-        sv.set_launch(args.threads, args.items, args.max_blocks, not args.no_streaming)
+    if args.threads or args.items or args.max_blocks or args.streaming >= 0:
+        sv.set_launch(args.threads, args.items, args.max_blocks,
+                      args.streaming if args.streaming >= 0 else 1)
     gdt = torch.bfloat16 if wl.grad_bf16 else torch.float32
     gbuf = [torch.empty(wl.d, dtype=gdt, device=dev) for _ in range(K)]
 

@@ -127,9 +127,10 @@ const char* dcasgd_strerror(int code);
 /*
  * Launch shape used by this handle's kernels.  threads: 64..512, a multiple
  * of 64; items: float4 groups per thread, one of 1, 2, 4; max_blocks: 0 = one
- * block per tile, otherwise blocks loop over tiles; streaming: non-zero marks
- * gradient reads and backup reads/writes non-temporal.  A zero/negative
- * threads or items keeps the current value.
+ * block per tile, otherwise blocks loop over tiles; streaming: 0 = plain
+ * accesses, 1 = gradient reads and backup reads/writes non-temporal, 2 = w
+ * and MeanSquare accesses non-temporal as well.  A zero/negative threads or
+ * items keeps the current value.
  */
 int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming);
 

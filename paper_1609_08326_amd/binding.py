@@ -147,9 +147,9 @@ class Server:
         return int(load().dcasgd_step(self._h))
 
     def set_launch(self, threads: int = 0, items: int = 0, max_blocks: int = 0,
-                   streaming: bool = True) -> None:
+                   streaming: int = 1) -> None:
         _check(load().dcasgd_set_launch(self._h, int(threads), int(items), int(max_blocks),
-                                        int(bool(streaming))), "dcasgd_set_launch")
+                                        int(streaming)), "dcasgd_set_launch")
 
     def push(self, worker: int, grad, stream=None) -> None:
         assert grad.is_cuda and grad.dtype == self.grad_dtype and grad.numel() == self.d

@@ -26,7 +26,7 @@ struct dcasgd_server {
     uint64_t t = 0;                   // pushes applied (Algorithm 2's t)
     std::vector<uint64_t> fresh_at;   // t at which w_bak(m) was last set to w
     int threads = 256, items = 2, max_blocks = 0;
-    bool streaming = true;
+    int streaming = 1;                // 0 plain, 1 gradient+backup non-temporal, 2 everything
     int last_error = DCASGD_OK;
 };
 
@@ -49,6 +49,13 @@ inline bool valid_items(int i) { return i == 1 || i == 2 || i == 4; }
 
 template <class F> inline void with_bool(bool v, F&& f) {
     if (v) f(std::true_type{}); else f(std::false_type{});
+}
+template <class F> inline void with_level(int v, F&& f) {
+    switch (v) {
+        case 0: f(std::integral_constant<int, 0>{}); break;
+        case 1: f(std::integral_constant<int, 1>{}); break;
+        default: f(std::integral_constant<int, 2>{}); break;
+    }
 }
 template <class F> inline void with_items(int v, F&& f) {
     switch (v) {
@@ -89,7 +96,7 @@ void launch_pull(dcasgd_t h, int worker, hipStream_t s) {
     float* row = h->bak + (size_t)worker * h->bak_stride;
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
     with_items(h->items, [&](auto IT) {
-        with_bool(h->streaming, [&](auto NT) {
+        with_bool(h->streaming != 0, [&](auto NT) {
             hipLaunchKernelGGL((pull_kernel<decltype(IT)::value, decltype(NT)::value>),
                                dim3(grid), dim3(h->threads), 0, s, h->w, row, n4, h->d);
         });
@@ -104,7 +111,7 @@ void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipSt
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(fuse_pull, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
-            with_bool(h->streaming, [&](auto NT) {
+            with_level(h->streaming, [&](auto NT) {
                 hipLaunchKernelGGL((push_kernel<decltype(AD)::value, decltype(BF)::value,
                                                 decltype(PL)::value, decltype(IT)::value,
                                                 decltype(NT)::value>),
@@ -131,7 +138,7 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
     with_bool(h->adaptive, [&](auto AD) {
       with_bool(h->grad_bf16, [&](auto BF) {
-        with_bool(h->streaming, [&](auto NT) {
+        with_bool(h->streaming != 0, [&](auto NT) {
             hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(BF)::value, 4,
                                                   decltype(NT)::value>),
                                dim3(grid), dim3(threads), 0, s, h->hp, h->w, h->ms, a, n4, h->d);
@@ -287,11 +294,11 @@ int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int st
     if (!h) return DCASGD_EINVAL;
     if (threads > 0 && !valid_threads(threads)) return fail(h, DCASGD_EINVAL);
     if (items > 0 && !valid_items(items)) return fail(h, DCASGD_EINVAL);
-    if (max_blocks < 0) return fail(h, DCASGD_EINVAL);
+    if (max_blocks < 0 || streaming < 0 || streaming > 2) return fail(h, DCASGD_EINVAL);
     if (threads > 0) h->threads = threads;
     if (items > 0) h->items = items;
     h->max_blocks = max_blocks;
-    h->streaming = streaming != 0;
+    h->streaming = streaming;
     return DCASGD_OK;
 }
 

@@ -118,7 +118,10 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
 // Work is cut into tiles of blockDim.x * ITEMS float4 groups; lane l of a tile
 // touches groups l, l + blockDim.x, ... so every wave-wide access is one
 // contiguous 1 KiB run.  Blocks walk tiles with stride gridDim.x.
-template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, bool NT, bool CHECKED>
+// NT: 0 = plain accesses, 1 = gradient and backup traffic non-temporal,
+// 2 = w and MeanSquare non-temporal as well (state too large to be re-read
+// from any cache before the next push).
+template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, int NT, bool CHECKED>
 __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w,
                                           float* __restrict__ ms, float* __restrict__ bak,
                                           const void* __restrict__ grad, size_t first,
@@ -128,10 +131,10 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
     for (int j = 0; j < ITEMS; ++j) {
         const size_t q = first + (size_t)j * blockDim.x;
         if (!CHECKED || q < n4) {
-            G[j] = load_grad4<BF16, NT>(grad, q);
-            B[j] = load4<NT>(bak, q);
-            W[j] = load4<false>(w, q);
-            if constexpr (ADAPTIVE) S[j] = load4<false>(ms, q);
+            G[j] = load_grad4<BF16, (NT >= 1)>(grad, q);
+            B[j] = load4<(NT >= 1)>(bak, q);
+            W[j] = load4<(NT >= 2)>(w, q);
+            if constexpr (ADAPTIVE) S[j] = load4<(NT >= 2)>(ms, q);
             else S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         } else {
             G[j] = B[j] = W[j] = S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -142,14 +145,14 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
         const size_t q = first + (size_t)j * blockDim.x;
         apply_push4<ADAPTIVE>(hp, G[j], B[j], W[j], S[j]);
         if (!CHECKED || q < n4) {
-            store4<false>(w, q, W[j]);
-            if constexpr (ADAPTIVE) store4<false>(ms, q, S[j]);
-            if constexpr (PULL) store4<NT>(bak, q, W[j]);
+            store4<(NT >= 2)>(w, q, W[j]);
+            if constexpr (ADAPTIVE) store4<(NT >= 2)>(ms, q, S[j]);
+            if constexpr (PULL) store4<(NT >= 1)>(bak, q, W[j]);
         }
     }
 }
 
-template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, bool NT>
+template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, int NT>
 __global__ void __launch_bounds__(512)
 push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __restrict__ bak,
             const void* __restrict__ grad, size_t n4, size_t d) {

@@ -56,7 +56,8 @@ def test_small_sizes_every_tail(mode, bf16, fused):
     for d in (1, 3, 4, 5, 255, 256, 1023, 1025, 2048 + 3, 40000 + 1):
         for launch in (None, dict(threads=64, items=1), dict(threads=128, items=4),
                        dict(threads=512, items=2, max_blocks=3),
-                       dict(threads=256, items=2, streaming=False)):
+                       dict(threads=256, items=2, streaming=0),
+                       dict(threads=256, items=1, streaming=2)):
             wl = small(d, mode=mode, bf16=bf16)
             say("small d=%d mode=%d bf16=%s fused=%s launch=%s" % (d, mode, bf16, fused, launch))
             run = GpuRun(wl, fused=fused, launch=launch)
