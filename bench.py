@@ -121,7 +121,7 @@ def main() -> int:
                   grad_bf16=wl.grad_bf16, pull_on_push=not batched)
     if args.threads or args.items or args.max_blocks or args.streaming >= 0:
         sv.set_launch(args.threads, args.items, args.max_blocks,
-                      args.streaming if args.streaming >= 0 else 1)
+                      args.streaming if args.streaming >= 0 else 2)
     gdt = torch.bfloat16 if wl.grad_bf16 else torch.float32
     gbuf = [torch.empty(wl.d, dtype=gdt, device=dev) for _ in range(K)]
 

@@ -130,7 +130,8 @@ const char* dcasgd_strerror(int code);
  * block per tile, otherwise blocks loop over tiles; streaming: 0 = plain
  * accesses, 1 = gradient reads and backup reads/writes non-temporal, 2 = w
  * and MeanSquare accesses non-temporal as well.  A zero/negative threads or
- * items keeps the current value.
+ * items keeps the current value.  Defaults: 256 threads (64 for the queue
+ * kernel), 2 items, one block per tile, streaming 2.
  */
 int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming);
 

@@ -147,7 +147,7 @@ class Server:
         return int(load().dcasgd_step(self._h))
 
     def set_launch(self, threads: int = 0, items: int = 0, max_blocks: int = 0,
-                   streaming: int = 1) -> None:
+                   streaming: int = 2) -> None:
         _check(load().dcasgd_set_launch(self._h, int(threads), int(items), int(max_blocks),
                                         int(streaming)), "dcasgd_set_launch")
 

@@ -12,6 +12,15 @@
 
 using namespace dcasgd;
 
+// Build-time tuning of the queue kernel: entries per load group, and whether
+// the next group's loads are issued ahead of the current group's arithmetic.
+#ifndef DCASGD_BATCH_KC
+#define DCASGD_BATCH_KC 4
+#endif
+#ifndef DCASGD_BATCH_PIPE
+#define DCASGD_BATCH_PIPE 1
+#endif
+
 struct dcasgd_server {
     size_t d = 0;
     int M = 0;
@@ -26,7 +35,8 @@ struct dcasgd_server {
     uint64_t t = 0;                   // pushes applied (Algorithm 2's t)
     std::vector<uint64_t> fresh_at;   // t at which w_bak(m) was last set to w
     int threads = 256, items = 2, max_blocks = 0;
-    int streaming = 1;                // 0 plain, 1 gradient+backup non-temporal, 2 everything
+    int batch_threads = 64;           // the queue kernel does 16x the work per lane: one wave per block
+    int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything
     int last_error = DCASGD_OK;
 };
 
@@ -134,13 +144,14 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
         a.bak[k - k0] = h->bak + (size_t)workers[k] * h->bak_stride;
     }
     const size_t n4 = h->d / 4;
-    const int threads = h->threads > 256 ? 256 : h->threads;
+    const int threads = h->batch_threads;
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
     with_bool(h->adaptive, [&](auto AD) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(BF)::value, 4,
-                                                  decltype(NT)::value>),
+            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(BF)::value,
+                                                  DCASGD_BATCH_KC, decltype(NT)::value,
+                                                  (DCASGD_BATCH_PIPE != 0)>),
                                dim3(grid), dim3(threads), 0, s, h->hp, h->w, h->ms, a, n4, h->d);
         });
       });
@@ -295,7 +306,10 @@ int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int st
     if (threads > 0 && !valid_threads(threads)) return fail(h, DCASGD_EINVAL);
     if (items > 0 && !valid_items(items)) return fail(h, DCASGD_EINVAL);
     if (max_blocks < 0 || streaming < 0 || streaming > 2) return fail(h, DCASGD_EINVAL);
-    if (threads > 0) h->threads = threads;
+    if (threads > 0) {
+        h->threads = threads;
+        h->batch_threads = threads > 256 ? 256 : threads;
+    }
     if (items > 0) h->items = items;
     h->max_blocks = max_blocks;
     h->streaming = streaming;

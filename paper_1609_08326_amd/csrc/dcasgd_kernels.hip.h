@@ -189,8 +189,22 @@ struct BatchArgs {
 
 // w and ms stay in registers across the queue; entry k reads its gradient and
 // its worker's backup, updates, and overwrites that backup with the new w.
-// Entries are handled KC at a time so that 2*KC 128-bit loads are in flight.
-template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool CHECKED>
+// Entries are handled KC at a time (2*KC 128-bit loads in flight per lane).
+// With PIPE the loads of the next group are issued before the arithmetic of
+// the current one, so the sqrt/divide work of one group hides the memory
+// latency of the next (the rows of a queue are distinct, so those loads do
+// not depend on the stores they overtake).
+template <bool BF16, int KC, bool NT>
+__device__ __forceinline__ void batch_load(const BatchArgs& a, int k0, size_t q,
+                                           f32x4 (&G)[KC], f32x4 (&B)[KC]) {
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+        G[kk] = load_grad4<BF16, NT>(a.grad[k0 + kk], q);
+        B[kk] = load4<NT>(a.bak[k0 + kk], q);
+    }
+}
+
+template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool PIPE, bool CHECKED>
 __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ w,
                                            float* __restrict__ ms, const BatchArgs& a,
                                            size_t q, size_t n4) {
@@ -198,31 +212,45 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
     f32x4 W = load4<false>(w, q);
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
-    int k0 = 0;
-    for (; k0 + KC <= a.K; k0 += KC) {
-        f32x4 G[KC], B[KC];
+    const int full = (a.K / KC) * KC;     // entries covered by whole groups
+    f32x4 G[KC], B[KC];
+    if constexpr (PIPE) {
+        f32x4 Gn[KC], Bn[KC];
+        if (full > 0) batch_load<BF16, KC, NT>(a, 0, q, G, B);
+        for (int k0 = 0; k0 < full; k0 += KC) {
+            const bool more = k0 + KC < full;
+            if (more) batch_load<BF16, KC, NT>(a, k0 + KC, q, Gn, Bn);
 #pragma unroll
-        for (int kk = 0; kk < KC; ++kk) {
-            G[kk] = load_grad4<BF16, NT>(a.grad[k0 + kk], q);
-            B[kk] = load4<NT>(a.bak[k0 + kk], q);
+            for (int kk = 0; kk < KC; ++kk) {
+                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S);
+                store4<NT>(a.bak[k0 + kk], q, W);
+            }
+            if (more) {
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) { G[kk] = Gn[kk]; B[kk] = Bn[kk]; }
+            }
         }
+    } else {
+        for (int k0 = 0; k0 < full; k0 += KC) {
+            batch_load<BF16, KC, NT>(a, k0, q, G, B);
 #pragma unroll
-        for (int kk = 0; kk < KC; ++kk) {
-            apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S);
-            store4<NT>(a.bak[k0 + kk], q, W);
+            for (int kk = 0; kk < KC; ++kk) {
+                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S);
+                store4<NT>(a.bak[k0 + kk], q, W);
+            }
         }
     }
-    for (; k0 < a.K; ++k0) {
-        const f32x4 G = load_grad4<BF16, NT>(a.grad[k0], q);
-        const f32x4 B = load4<NT>(a.bak[k0], q);
-        apply_push4<ADAPTIVE>(hp, G, B, W, S);
-        store4<NT>(a.bak[k0], q, W);
+    for (int k = full; k < a.K; ++k) {
+        const f32x4 g = load_grad4<BF16, NT>(a.grad[k], q);
+        const f32x4 b = load4<NT>(a.bak[k], q);
+        apply_push4<ADAPTIVE>(hp, g, b, W, S);
+        store4<NT>(a.bak[k], q, W);
     }
     store4<false>(w, q, W);
     if constexpr (ADAPTIVE) store4<false>(ms, q, S);
 }
 
-template <bool ADAPTIVE, bool BF16, int KC, bool NT>
+template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool PIPE>
 __global__ void __launch_bounds__(256)
 push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, BatchArgs a,
                   size_t n4, size_t d) {
@@ -230,9 +258,9 @@ push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, Batch
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t q = tile * blockDim.x + threadIdx.x;
         if ((tile + 1) * blockDim.x <= n4)
-            batch_quad<ADAPTIVE, BF16, KC, NT, false>(hp, w, ms, a, q, n4);
+            batch_quad<ADAPTIVE, BF16, KC, NT, PIPE, false>(hp, w, ms, a, q, n4);
         else
-            batch_quad<ADAPTIVE, BF16, KC, NT, true>(hp, w, ms, a, q, n4);
+            batch_quad<ADAPTIVE, BF16, KC, NT, PIPE, true>(hp, w, ms, a, q, n4);
     }
     if (blockIdx.x == 0) {
         const size_t i = 4 * n4 + threadIdx.x;
@@ -411,9 +439,11 @@ synth_grad_kernel(const float* __restrict__ snap, const float* __restrict__ hdia
         for (int j = 0; j < ITEMS; ++j) {
             const size_t q = first + (size_t)j * blockDim.x;
             if (q < n4) {
-                A[j] = load4<true>(snap, q);
-                H[j] = load4<false>(hdiag, q);
-                O[j] = load4<false>(wstar, q);
+                // the snapshot is read again by the push that follows: leave it
+                // cacheable; the loss vectors stream through once per arrival
+                A[j] = load4<false>(snap, q);
+                H[j] = load4<true>(hdiag, q);
+                O[j] = load4<true>(wstar, q);
             } else {
                 A[j] = H[j] = O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
