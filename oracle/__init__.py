@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.oracle_set_ms.restype = None
         L.oracle_get_bak.argtypes = [vp, C.c_int, f32p]
         L.oracle_get_bak.restype = C.c_int
+        L.oracle_sync_fold.argtypes = [vp, f32p, C.c_int, C.c_float]
+        L.oracle_sync_fold.restype = C.c_int
         L.oracle_synth_grad.argtypes = [f32p, f32p, f32p, C.c_float, C.c_uint64, C.c_uint32,
                                         u64p, C.c_int, f32p, C.c_size_t]
         L.oracle_synth_grad.restype = None
@@ -167,6 +169,14 @@ class Server:
         if lib().oracle_pull(self._h, int(worker)) != 0:
             raise ValueError("bad worker id")
         return self.bak(worker)
+
+    def sync_fold(self, grads, eta_hat: float) -> None:
+        """Supplement's synchronous variant: fold the rows of ``grads`` (J x n, all taken
+        at the current model) into the model with step eta_hat/J, in row order."""
+        g = np.ascontiguousarray(grads, dtype=np.float32)
+        assert g.ndim == 2 and g.shape[1] == self.n
+        if lib().oracle_sync_fold(self._h, _fp(g), int(g.shape[0]), float(eta_hat)) != 0:
+            raise ValueError("sync_fold needs at least one gradient")
 
     def w(self) -> np.ndarray:
         out = np.zeros(self.n, dtype=np.float32)

@@ -12,6 +12,11 @@
 //     constant lambda (DC-ASGD-c, Section 6) or with lambda_t = lambda_0 /
 //     sqrt(MeanSquare(t) + eps) where MeanSquare follows Eq. 18 (DC-ASGD-a);
 //   * the "pull request" branch: w_bak(m) <- w_t;
+//   * the synchronous variant of the supplement ("Large Mini-batch Synchronous
+//     SGD with Delay-Compensated Gradient"): J gradients taken at the same
+//     model w_t are applied one after the other with step eta_hat/J, each
+//     compensated for the distance the running model has already moved from
+//     w_t;
 //   * a stand-in for the worker of Algorithm 1 ("compute gradient"): the
 //     gradient of a diagonal quadratic loss at the worker's snapshot plus
 //     seeded Gaussian noise. This part is not from the paper; it is the
@@ -32,6 +37,10 @@
 //   * (1 - m) of Eq. 18 is formed once, in binary32.
 //   * the compensation term is grouped (lambda * g*g) * (w - w_bak): the
 //     diagonal Hessian estimate lambda g.g of Section 4 is formed first.
+//   * in the synchronous fold the order of the J gradients is the caller's
+//     (the supplement only suggests ordering by distance from w_t); lambda
+//     may be the adaptive one, MeanSquare then advances once per gradient;
+//     eta_hat/J is formed once in binary32.
 //
 // Pins (see tests/test_oracle_*.py): lambda = 0 gives ASGD (Eq. 2.2); M = 1
 // gives sequential SGD; exact-rational hand trace; closed forms for a
@@ -215,6 +224,27 @@ void pull_range(Server& sv, int m, size_t lo, size_t hi) {
     for (size_t i = lo; i < hi; ++i) sv.bak[m][i] = sv.w[i];
 }
 
+// Supplement, last section: fold J gradients g[0..J) (each n floats, all taken
+// at the model held on entry, w_t) into the model:
+//   wt^{j+1} = wt^j - (eta_hat/J) * (g_j + lambda g_j.g_j.(wt^j - w_t)),  wt^0 = w_t.
+// This is the push rule with the learning rate eta_hat/J and with w_t in the
+// role of the backup for every j.
+void sync_fold(Server& sv, const float* const* g, int J, float eta_hat) {
+    Server step_rule = Server();            // same hyper-parameters, other learning rate
+    step_rule.lambda0 = sv.lambda0;
+    step_rule.ema_m = sv.ema_m;
+    step_rule.one_minus_m = sv.one_minus_m;
+    step_rule.eps = sv.eps;
+    step_rule.eta = eta_hat / (float)J;
+    for (size_t i = 0; i < sv.n; ++i) {
+        const float anchor = sv.w[i];       // w_t
+        for (int j = 0; j < J; ++j) {
+            if (sv.adaptive) push_elem_adaptive(step_rule, g[j][i], anchor, &sv.w[i], &sv.ms[i]);
+            else             push_elem_const(step_rule, g[j][i], anchor, &sv.w[i]);
+        }
+    }
+}
+
 // Stand-in worker (Algorithm 1, "compute gradient") for elements [lo, hi):
 //   g_i = h_i * (snapshot_i - wstar_i) + sigma * z(seed, t, global index of i)
 // optionally rounded to bfloat16 and widened again. gidx maps local element
@@ -345,6 +375,19 @@ int oracle_get_bak(void* h, int worker, float* out) {
 void oracle_set_ms(void* h, const float* in) {
     Server& sv = *static_cast<Server*>(h);
     sv.ms.assign(in, in + sv.n);
+}
+
+// Synchronous delay-compensated fold of J gradients (g: J*n floats, gradient
+// j at g + j*n), all taken at the current model.  t advances by J.
+int oracle_sync_fold(void* h, const float* g, int J, float eta_hat) {
+    Server& sv = *static_cast<Server*>(h);
+    if (J < 1 || !g) return -1;
+    KeepDenormals guard;
+    std::vector<const float*> rows((size_t)J);
+    for (int j = 0; j < J; ++j) rows[(size_t)j] = g + (size_t)j * sv.n;
+    sync_fold(sv, rows.data(), J, eta_hat);
+    sv.t += (uint64_t)J;
+    return 0;
 }
 
 // Synthetic worker gradient taken at an arbitrary snapshot (n floats each).

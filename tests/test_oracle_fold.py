@@ -1,0 +1,107 @@
+"""Pins for the oracle's synchronous delay-compensated fold (the supplement's
+"Large Mini-batch Synchronous SGD with Delay-Compensated Gradient")."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import MODE_A, MODE_C
+
+F32 = np.float32
+
+
+def test_lambda_zero_is_large_minibatch_ssgd():
+    """Without compensation the fold is one synchronous step with the averaged
+    gradient: w - eta_hat * (1/J) * sum_j g_j (the supplement's large-batch rule)."""
+    rng = np.random.default_rng(0)
+    n, J, eta_hat = 301, 8, 0.8
+    w0 = rng.standard_normal(n).astype(F32)
+    g = rng.standard_normal((J, n)).astype(F32)
+    sv = oracle.Server(w0, 1, 0.123, 0.0, MODE_C)
+    sv.sync_fold(g, eta_hat)
+    step = F32(F32(eta_hat) / F32(J))
+    w = w0.copy()
+    for j in range(J):                       # same sum, taken one gradient at a time
+        w = (w - (step * g[j]).astype(F32)).astype(F32)
+    assert np.array_equal(sv.w(), w)
+    exact = w0.astype(np.float64) - eta_hat * g.astype(np.float64).mean(axis=0)
+    assert np.max(np.abs(sv.w() - exact)) < 1e-5
+    assert sv.t == J
+
+
+@pytest.mark.parametrize("mode", [MODE_C, MODE_A])
+def test_single_gradient_is_plain_sgd(mode):
+    rng = np.random.default_rng(1)
+    n = 100
+    w0 = rng.standard_normal(n).astype(F32)
+    g = rng.standard_normal((1, n)).astype(F32)
+    sv = oracle.Server(w0, 1, 0.5, 2.0, mode, ema_m=0.9, eps=1e-7)
+    sv.sync_fold(g, 0.25)
+    assert np.array_equal(sv.w(), (w0 - (F32(0.25) * g[0]).astype(F32)).astype(F32))
+
+
+def test_hand_worked_fold():
+    """lambda = 1/4, eta_hat = 1, J = 2 (step 1/2), w_t = 1, g = (2, 4):
+    j=0: moved 0      -> w = 1 - 0.5*2 = 0
+    j=1: moved 0-1=-1 -> compensated 4 + 0.25*16*(-1) = 0 -> w stays 0."""
+    sv = oracle.Server(np.array([1.0], dtype=F32), 1, 9.0, 0.25, MODE_C)
+    sv.sync_fold(np.array([[2.0], [4.0]], dtype=F32), 1.0)
+    assert float(sv.w()[0]) == 0.0
+    # the other order: j=0: w = 1 - 0.5*4 = -1; j=1: moved -2 -> 2 + 0.25*4*(-2) = 0 -> w = -1
+    sv = oracle.Server(np.array([1.0], dtype=F32), 1, 9.0, 0.25, MODE_C)
+    sv.sync_fold(np.array([[4.0], [2.0]], dtype=F32), 1.0)
+    assert float(sv.w()[0]) == -1.0
+
+
+def test_exact_rational_brute_force():
+    rng = np.random.default_rng(2)
+    n, J = 8, 4
+    lam, eta_hat = Fraction(1, 4), Fraction(2)
+    w0 = (rng.integers(-8, 9, n) / 4).astype(F32)
+    g = (rng.choice([-1.0, 1.0], (J, n)) * 2.0 ** rng.integers(-1, 2, (J, n))).astype(F32)
+    sv = oracle.Server(w0, 1, 0.5, float(lam), MODE_C)
+    sv.sync_fold(g, float(eta_hat))
+    step = eta_hat / J
+    for i in range(n):
+        wt = Fraction(float(w0[i]))
+        w = wt
+        for j in range(J):
+            gj = Fraction(float(g[j, i]))
+            w = w - step * (gj + lam * gj * gj * (w - wt))
+        assert Fraction(float(sv.w()[i])) == w
+
+
+def test_fold_reproduces_sequential_sgd_when_lambda_g2_is_the_curvature():
+    """The supplement's point: with an exact first-order term the fold of J
+    same-snapshot gradients equals J sequential SGD steps with learning rate
+    eta_hat/J on the samples in the same order.  Quadratic sample loss
+    0.5*h*(w - c_j)^2, gradient at w_t: g_j = h (w_t - c_j); choose c_j so that
+    g_j = +-2 and lambda = 1/4, h = 1: lambda g_j^2 = h."""
+    h, lam, eta_hat, J, w_t = 1.0, 0.25, 2.0, 4, 0.5
+    signs = [1.0, -1.0, -1.0, 1.0]
+    c = [w_t - s * 2.0 / h for s in signs]
+    g = np.array([[h * (w_t - cj)] for cj in c], dtype=F32)
+    sv = oracle.Server(np.array([w_t], dtype=F32), 1, 0.0, lam, MODE_C)
+    sv.sync_fold(g, eta_hat)
+    w = w_t
+    for cj in c:                                   # sequential SGD, gradient at the running model
+        w = w - (eta_hat / J) * h * (w - cj)
+    assert float(sv.w()[0]) == w
+    # and uncompensated large-batch SGD lands elsewhere
+    plain = w_t - eta_hat * float(np.mean(g))
+    assert plain != w
+
+
+def test_adaptive_fold_advances_mean_square_per_gradient():
+    m, eps, lam0 = 0.75, 0.0, 0.25
+    sv = oracle.Server(np.array([1.0], dtype=F32), 1, 0.0, lam0, MODE_A, ema_m=m, eps=eps)
+    sv.sync_fold(np.array([[2.0], [2.0]], dtype=F32), 1.0)
+    # j=0: MS = 0.25*4 = 1, lambda = 0.25, moved 0 -> w = 1 - 0.5*2 = 0
+    # j=1: MS = 0.75 + 1 = 1.75, lambda = 0.25/sqrt(1.75), moved -1
+    ms = 1.75
+    lam = np.float32(lam0) / np.sqrt(np.float32(ms))
+    w = 0.0 - 0.5 * (2.0 + float(lam) * 4.0 * (-1.0))
+    assert float(sv.ms()[0]) == ms
+    assert abs(float(sv.w()[0]) - w) < 1e-6
+    assert sv.t == 2
