@@ -35,6 +35,8 @@ def algorithmic_bytes_per_update(wl) -> float:
     backup (+MeanSquare).  Queue of K: w/MeanSquare once per queue."""
     g = 2 if wl.grad_bf16 else 4
     adaptive = wl.mode == 1
+    if wl.order == "sync":      # fold: w (+MeanSquare) once, K gradients, no backups
+        return ((16 if adaptive else 8) + wl.K * g) / wl.K
     if wl.K > 1:
         per_queue = (16 if adaptive else 8) + wl.K * (g + 4 + 4)
         return per_queue / wl.K
@@ -107,7 +109,8 @@ def main() -> int:
     from paper_1609_08326_amd import workloads as W
 
     wl = W.get(args.workload)
-    batched = wl.K > 1
+    sync = wl.order == "sync"
+    batched = wl.K > 1 and not sync
     K = wl.K
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -135,11 +138,13 @@ def main() -> int:
         if rec:
             rec[0].record()
         for j, m in enumerate(ms_):
-            B.synth_grad(sv.snapshot(m), hd, ws, wl.sigma, wl.seed, base + j, gbuf[j],
-                         threads=args.synth_threads, items=args.synth_items)
+            B.synth_grad(sv.w if sync else sv.snapshot(m), hd, ws, wl.sigma, wl.seed, base + j,
+                         gbuf[j], threads=args.synth_threads, items=args.synth_items)
         if rec:
             rec[1].record()
-        if batched:
+        if sync:
+            sv.sync_fold(gbuf, wl.eta * K)
+        elif batched:
             sv.push_batch(ms_, gbuf)
         else:
             sv.push(ms_[0], gbuf[0])
@@ -158,7 +163,7 @@ def main() -> int:
     updates = wl.d * K * n_steps
     value = updates / elapsed
     bpu = algorithmic_bytes_per_update(wl)
-    kname = "push_batch_K%d" % K if batched else "push_fused"
+    kname = "sync_fold_J%d" % K if sync else "push_batch_K%d" % K if batched else "push_fused"
     out = {
         "metric": "element-updates/sec",
         "value": value,
@@ -174,7 +179,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "M": wl.M, "K": K,
                    "variant": "DC-ASGD-a" if wl.mode == 1 else "DC-ASGD-c",
-                   "step": "synth_grad x%d + fused push+pull" % K},
+                   "step": ("synth_grad x%d + synchronous fold" if sync else
+                            "synth_grad x%d + fused push+pull") % K},
     }
     if use_events:
         synth_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / n_steps
@@ -192,7 +198,7 @@ def main() -> int:
         synth_bytes = (12 + (2 if wl.grad_bf16 else 4)) * wl.d * K
         out["worker_kernel"] = {"kernel": "synth_grad", "avg_ms_per_step": synth_ms,
                                 "achieved_GBs": synth_bytes / (synth_ms * 1e-3) / 1e9}
-    if args.cpu_seconds > 0:
+    if args.cpu_seconds > 0 and not sync:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(out), flush=True)
     return 0

@@ -107,6 +107,20 @@ int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads,
                       int K, void* stream);
 
 /*
+ * Synchronous variant of the supplement ("Large Mini-batch Synchronous SGD
+ * with Delay-Compensated Gradient"): J gradients (1 <= J <= DCASGD_MAX_K, host
+ * array of device pointers as for dcasgd_push), all taken at the current
+ * model w_t, are folded into w one after the other in the given order:
+ *   wt^{j+1} = wt^j - (eta_hat/J) * (g_j + lambda g_j*g_j*(wt^j - w_t)),  wt^0 = w_t
+ * i.e. the push rule above with eta = eta_hat/J (formed once in binary32) and
+ * b = w_t for every j; in MODE_A MeanSquare advances once per gradient.  One
+ * pass per element with w_t, w and ms in registers; backups are not touched;
+ * t advances by J.  The order heuristic the supplement mentions (by distance
+ * from w_t) is left to the caller.
+ */
+int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream);
+
+/*
  * Algorithm 2, "pull request": w_bak(worker) <- w, enqueued on the stream of
  * the most recent init/push on this handle, and returns the device pointer of
  * that backup row, which is what "send w_t back to worker m" hands over.  If

@@ -32,6 +32,8 @@ _PROTOTYPES = {
     "dcasgd_push": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
     "dcasgd_push_batch": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_void_p),
                                     C.c_int, C.c_void_p]),
+    "dcasgd_sync_fold": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
+                                   C.c_void_p]),
     "dcasgd_pull": (C.c_void_p, [C.c_void_p, C.c_int]),
     "dcasgd_step": (C.c_uint64, [C.c_void_p]),
     "dcasgd_last_error": (C.c_int, [C.c_void_p]),
@@ -165,6 +167,15 @@ class Server:
         ga = (C.c_void_p * K)(*[g.data_ptr() for g in grads])
         _check(load().dcasgd_push_batch(self._h, wa, ga, K, _stream_ptr(stream)),
                "dcasgd_push_batch")
+
+    def sync_fold(self, grads: Sequence, eta_hat: float, stream=None) -> None:
+        """Fold J same-snapshot gradients into w (the supplement's synchronous variant)."""
+        J = len(grads)
+        for g in grads:
+            assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
+        ga = (C.c_void_p * J)(*[g.data_ptr() for g in grads])
+        _check(load().dcasgd_sync_fold(self._h, ga, J, float(eta_hat), _stream_ptr(stream)),
+               "dcasgd_sync_fold")
 
     def pull(self, worker: int):
         """Refresh worker's backup from w and return it (a view of row `worker`)."""

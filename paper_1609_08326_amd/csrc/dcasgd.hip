@@ -274,6 +274,37 @@ int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads, 
     return launched(h);
 }
 
+int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (!grads || J < 1 || J > DCASGD_MAX_K || !std::isfinite(eta_hat))
+        return fail(h, DCASGD_EINVAL);
+    FoldArgs a{};
+    a.J = J;
+    for (int j = 0; j < J; ++j) {
+        if (int rc = check_grad(h, grads[j])) return fail(h, rc);
+        a.grad[j] = grads[j];
+    }
+    Hyper hp = h->hp;
+    hp.eta = eta_hat / (float)J;            // per-gradient step, formed once in binary32
+    const size_t n4 = h->d / 4;
+    const int threads = h->batch_threads;
+    const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    with_bool(h->adaptive, [&](auto AD) {
+      with_bool(h->grad_bf16, [&](auto BF) {
+        with_bool(h->streaming != 0, [&](auto NT) {
+            hipLaunchKernelGGL((sync_fold_kernel<decltype(AD)::value, decltype(BF)::value, 4,
+                                                 decltype(NT)::value>),
+                               dim3(grid), dim3(threads), 0, s, hp, h->w, h->ms, a, n4, h->d);
+        });
+      });
+    });
+    h->stream = s;
+    h->t += (uint64_t)J;
+    return launched(h);
+}
+
 const float* dcasgd_pull(dcasgd_t h, int worker) {
     if (!h) return nullptr;
     if (!h->ready) { fail(h, DCASGD_ESTATE); return nullptr; }

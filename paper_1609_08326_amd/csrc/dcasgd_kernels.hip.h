@@ -278,6 +278,69 @@ push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, Batch
     }
 }
 
+// ---- synchronous delay-compensated fold (supplement, large mini-batch SSGD) ------
+// J gradients taken at the same model w_t are applied one after the other;
+// entry j is compensated for the distance the running model has moved from
+// w_t.  Per parameter w_t is simply the value loaded on entry, so it stays in
+// a register: the only traffic is w, MeanSquare and the J gradients.  hp.eta
+// holds the per-gradient step eta_hat / J.
+struct FoldArgs {
+    const void* grad[16];
+    int J;
+};
+
+template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool CHECKED>
+__device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w,
+                                          float* __restrict__ ms, const FoldArgs& a,
+                                          size_t q, size_t n4) {
+    if (CHECKED && q >= n4) return;
+    const f32x4 anchor = load4<false>(w, q);
+    f32x4 W = anchor;
+    f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (ADAPTIVE) S = load4<false>(ms, q);
+    const int full = (a.J / KC) * KC;
+    for (int j0 = 0; j0 < full; j0 += KC) {
+        f32x4 G[KC];
+#pragma unroll
+        for (int jj = 0; jj < KC; ++jj) G[jj] = load_grad4<BF16, NT>(a.grad[j0 + jj], q);
+#pragma unroll
+        for (int jj = 0; jj < KC; ++jj) apply_push4<ADAPTIVE>(hp, G[jj], anchor, W, S);
+    }
+    for (int j = full; j < a.J; ++j) {
+        const f32x4 g = load_grad4<BF16, NT>(a.grad[j], q);
+        apply_push4<ADAPTIVE>(hp, g, anchor, W, S);
+    }
+    store4<false>(w, q, W);
+    if constexpr (ADAPTIVE) store4<false>(ms, q, S);
+}
+
+template <bool ADAPTIVE, bool BF16, int KC, bool NT>
+__global__ void __launch_bounds__(256)
+sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldArgs a,
+                 size_t n4, size_t d) {
+    const size_t ntiles = (n4 + blockDim.x - 1) / blockDim.x;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t q = tile * blockDim.x + threadIdx.x;
+        if ((tile + 1) * blockDim.x <= n4)
+            fold_quad<ADAPTIVE, BF16, KC, NT, false>(hp, w, ms, a, q, n4);
+        else
+            fold_quad<ADAPTIVE, BF16, KC, NT, true>(hp, w, ms, a, q, n4);
+    }
+    if (blockIdx.x == 0) {
+        const size_t i = 4 * n4 + threadIdx.x;
+        if (i < d) {
+            const float anchor = w[i];
+            float wi = anchor;
+            float si = 0.f;
+            if constexpr (ADAPTIVE) si = ms[i];
+            for (int j = 0; j < a.J; ++j)
+                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[j], i), anchor, wi, si);
+            w[i] = wi;
+            if constexpr (ADAPTIVE) ms[i] = si;
+        }
+    }
+}
+
 // ---- pull: w_bak(m) <- w ---------------------------------------------------------
 template <int ITEMS, bool NT>
 __global__ void __launch_bounds__(512)

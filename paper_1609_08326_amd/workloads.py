@@ -83,7 +83,7 @@ class Workload:
                      (a worker has one gradient in flight, Algorithm 1), every
                      block a fresh random choice and order.
         """
-        if self.order == "round_robin":
+        if self.order in ("round_robin", "sync"):
             return (np.arange(self.T) % self.M).astype(np.int32)
         rng = self._rng(3)
         if self.order == "iid":
@@ -127,10 +127,19 @@ CONFIGS = (
 )
 
 
+# Beyond the five asynchronous configurations: the supplement's synchronous
+# variant, 16 same-snapshot gradients folded per step (eta_hat = K * eta).
+EXTRA = (
+    Workload("fold_resnet50_J16_a", d=25_557_032, M=1, T=320, mode=MODE_A, eta=0.05,
+             lambda0=2.0, ema_m=0.95, eps=1e-7, h_lo=1e-4, h_hi=1.0, wstar_sigma=0.05,
+             sigma=0.001, order="sync", K=16, seed=_BASE_SEED + 5),
+)
+
+
 def get(name_or_index) -> Workload:
     if isinstance(name_or_index, int):
         return CONFIGS[name_or_index]
-    for wl in CONFIGS:
+    for wl in CONFIGS + EXTRA:
         if wl.name == name_or_index or wl.name.startswith(str(name_or_index)):
             return wl
     raise KeyError(name_or_index)

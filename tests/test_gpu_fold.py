@@ -1,0 +1,98 @@
+"""GPU parity for the synchronous delay-compensated fold (supplement): bitwise
+against the oracle, through the C ABI."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1609_08326_amd import workloads as W
+
+from gpu_harness import assert_same_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_fold_small_sizes(mode, bf16):
+    import torch
+    from paper_1609_08326_amd import binding as B
+    rng = np.random.default_rng(17)
+    lam0 = 2.0 if mode == W.MODE_A else 0.04
+    for d in (1, 3, 4, 257, 4096 + 2, 70001):
+        for J in (1, 2, 5, 16):
+            say("fold d=%d J=%d mode=%d bf16=%s" % (d, J, mode, bf16))
+            w0 = rng.standard_normal(d).astype(np.float32)
+            sv = B.Server(torch.from_numpy(w0).cuda(), 2, 0.1, lam0, mode, 0.95, 1e-7,
+                          grad_bf16=bf16)
+            ref = oracle.Server(w0, 2, 0.1, lam0, mode, 0.95, 1e-7)
+            for rnd in range(3):
+                g = (0.3 * rng.standard_normal((J, d))).astype(np.float32)
+                if bf16:
+                    gt = torch.from_numpy(g).to(torch.bfloat16)
+                    g = gt.float().numpy()
+                    dev = [gt[j].contiguous().cuda() for j in range(J)]
+                else:
+                    dev = [torch.from_numpy(g[j]).cuda() for j in range(J)]
+                sv.sync_fold(dev, 0.1 * J)
+                ref.sync_fold(g, 0.1 * J)
+            torch.cuda.synchronize()
+            assert sv.t == ref.t == 3 * J
+            assert_same_bits(sv.w.cpu().numpy(), ref.w(), "fold w d=%d J=%d" % (d, J))
+            if mode == W.MODE_A:
+                assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "fold ms d=%d J=%d" % (d, J))
+            assert_same_bits(sv.bak[:, :d].cpu().numpy().ravel(), np.tile(w0, 2), "backups untouched")
+
+
+def test_fold_full_size_sampled():
+    """The benchmark's fold workload at full size; the oracle follows a sample."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = W.get("fold")
+    say("fold full size %s" % wl.name)
+    hd_h, ws_h = wl.hdiag(), wl.wstar()
+    hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode,
+                  wl.ema_m, wl.eps)
+    idx = wl.sample_indices(100_000, edge=4096)
+    ii = idx.astype(np.int64)
+    ref = oracle.Server(wl.w0()[ii], wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+    gbuf = [torch.empty(wl.d, device="cuda") for _ in range(wl.K)]
+    rounds = 3
+    for r in range(rounds):
+        for j in range(wl.K):
+            B.synth_grad(sv.w, hd, ws, wl.sigma, wl.seed, r * wl.K + j, gbuf[j])
+        sv.sync_fold(gbuf, wl.eta * wl.K)
+        w_t = ref.w()
+        g = np.stack([oracle.synth_grad(w_t, hd_h[ii], ws_h[ii], wl.sigma, wl.seed,
+                                        r * wl.K + j, gidx=idx) for j in range(wl.K)])
+        ref.sync_fold(g, wl.eta * wl.K)
+    torch.cuda.synchronize()
+    assert_same_bits(sv.w.cpu().numpy()[ii], ref.w(), "fold w (sampled)")
+    assert_same_bits(sv.ms.cpu().numpy()[ii], ref.ms(), "fold ms (sampled)")
+    assert np.all(np.isfinite(sv.w.cpu().numpy()))
+
+
+def test_fold_rejects_bad_arguments():
+    import ctypes as C
+    import torch
+    from paper_1609_08326_amd import binding as B
+    lib = B.load()
+    sv = B.Server(torch.zeros(1000, device="cuda"), 1, 0.1, 0.04, B.MODE_C)
+    g = torch.ones(1008, device="cuda")
+    s = int(torch.cuda.current_stream().cuda_stream)
+    ga = (C.c_void_p * 17)(*([g.data_ptr()] * 17))
+    assert lib.dcasgd_sync_fold(sv._h, ga, 0, 0.1, s) == B.EINVAL
+    assert lib.dcasgd_sync_fold(sv._h, ga, 17, 0.1, s) == B.EINVAL
+    assert lib.dcasgd_sync_fold(sv._h, None, 2, 0.1, s) == B.EINVAL
+    assert lib.dcasgd_sync_fold(sv._h, ga, 2, float("inf"), s) == B.EINVAL
+    bad = (C.c_void_p * 2)(g.data_ptr(), g.data_ptr() + 4)
+    assert lib.dcasgd_sync_fold(sv._h, bad, 2, 0.1, s) == B.EALIGN
+    torch.cuda.synchronize()
+    assert sv.t == 0 and float(sv.w.abs().max()) == 0.0
