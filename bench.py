@@ -27,6 +27,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+# plain (unpacked, non-FMA-counted) vector issue: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
+VALU_PEAK_TLANE = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
 def algorithmic_bytes_per_update(wl) -> float:
@@ -43,11 +45,12 @@ def algorithmic_bytes_per_update(wl) -> float:
     return (4 + 4 + g + 4 + 4) + (8 if adaptive else 0)
 
 
-def read_traffic(name: str):
-    """HBM bytes per launch from the committed counter summary, if any."""
+def read_profile(name: str, key: str = "traffic_bytes_per_launch"):
+    """A per-launch figure (HBM bytes, VALU instructions) from the committed
+    rocprofv3 counter summary of this kernel and workload, if there is one."""
     path = os.path.join(ROOT, "profiles", "pmc_%s.txt" % name)
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        m = re.search(r"^%s:\s*([0-9.eE+]+)" % key, open(path).read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
@@ -189,10 +192,22 @@ def main() -> int:
         achieved = launch_bytes / (push_ms * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": achieved,
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                           "traffic": read_traffic("%s_%s" % (kname, wl.name.split("_")[0])),
+                           "traffic": read_profile("%s_%s" % (kname, wl.name.split("_")[0])),
                            "avg_launch_ms": push_ms,
                            "algorithmic_bytes_per_launch": launch_bytes,
                            "bytes_per_element_update": bpu}
+        valu = read_profile("%s_%s" % (kname, wl.name.split("_")[0]), "valu_instr_per_launch")
+        if sync and valu:
+            # the fold moves 5 B per update and is bound by vector issue instead:
+            # measured wavefront VALU instructions per launch x 64 lanes / time
+            lane_rate = valu * 64 / (push_ms * 1e-3) / 1e12
+            out["roofline"] = {"bound": "alu", "kernel": kname, "achieved": lane_rate,
+                               "peak": VALU_PEAK_TLANE, "unit": "T lane-instr/s",
+                               "frac": lane_rate / VALU_PEAK_TLANE,
+                               "traffic": out["roofline"]["traffic"], "avg_launch_ms": push_ms,
+                               "hbm_achieved_GBs": achieved,
+                               "algorithmic_bytes_per_launch": launch_bytes,
+                               "bytes_per_element_update": bpu}
         out["server_update_only"] = {"value": wl.d * K / (push_ms * 1e-3),
                                      "unit": "element-updates/s"}
         synth_bytes = (12 + (2 if wl.grad_bf16 else 4)) * wl.d * K
