@@ -97,6 +97,9 @@ def main() -> int:
     ap.add_argument("--streaming", type=int, default=-1, help="0, 1 or 2 (see dcasgd_set_launch)")
     ap.add_argument("--synth-threads", type=int, default=0)
     ap.add_argument("--synth-items", type=int, default=0)
+    ap.add_argument("--fused-worker", action="store_true",
+                    help="also time the worker+push fusion (dcasgd_push_synth) and report it "
+                         "under 'fused_worker_path'; K=1 workloads only")
     ap.add_argument("--no-events", action="store_true",
                     help="skip per-kernel events (whole-path timing only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
@@ -213,6 +216,24 @@ def main() -> int:
         synth_bytes = (12 + (2 if wl.grad_bf16 else 4)) * wl.d * K
         out["worker_kernel"] = {"kernel": "synth_grad", "avg_ms_per_step": synth_ms,
                                 "achieved_GBs": synth_bytes / (synth_ms * 1e-3) / 1e9}
+    if args.fused_worker and K == 1:
+        # same arrivals, one launch per arrival: the gradient never leaves registers
+        torch.cuda.synchronize()
+        for i in range(n_warm):
+            sv.push_synth(int(arrivals[i]), hd, ws, wl.sigma, wl.seed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_steps):
+            sv.push_synth(int(arrivals[n_warm + i]), hd, ws, wl.sigma, wl.seed)
+        torch.cuda.synchronize()
+        fe = time.perf_counter() - t0
+        fbytes = (32 + (0 if wl.mode == 1 else -8)) * wl.d
+        out["fused_worker_path"] = {"value": wl.d * n_steps / fe, "unit": "element-updates/s",
+                                    "ms_per_step": 1e3 * fe / n_steps,
+                                    "algorithmic_GBs": fbytes * n_steps / fe / 1e9,
+                                    "bytes_per_element_update": fbytes / wl.d,
+                                    "note": "synthetic workload only: worker gradient formed in "
+                                            "registers inside the push kernel"}
     if args.cpu_seconds > 0 and not sync:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(out), flush=True)

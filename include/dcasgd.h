@@ -165,6 +165,18 @@ int dcasgd_synth_grad(const float* snap, const float* hdiag, const float* wstar,
                       void* grad_out, int as_bf16, size_t d, void* stream,
                       int threads, int items);
 
+/*
+ * Synthetic workload only: worker and push in one pass.  Equivalent to
+ *   dcasgd_synth_grad(w_bak(worker), hdiag, wstar, sigma, seed, push_idx = t, g, ...);
+ *   dcasgd_push(h, worker, g, stream);
+ * (same bits, gradient rounded to bfloat16 in between if DCASGD_GRAD_BF16)
+ * but the gradient stays in registers: 32 bytes of traffic per parameter
+ * instead of 16 + 28.  hdiag, wstar: device pointers, d floats, 16-byte
+ * aligned, not overlapping the bound state.  Honours DCASGD_PULL_ON_PUSH.
+ */
+int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* wstar,
+                      float sigma, uint64_t seed, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,6 +34,8 @@ _PROTOTYPES = {
                                     C.c_int, C.c_void_p]),
     "dcasgd_sync_fold": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
                                    C.c_void_p]),
+    "dcasgd_push_synth": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
+                                    C.c_uint64, C.c_void_p]),
     "dcasgd_pull": (C.c_void_p, [C.c_void_p, C.c_int]),
     "dcasgd_step": (C.c_uint64, [C.c_void_p]),
     "dcasgd_last_error": (C.c_int, [C.c_void_p]),
@@ -167,6 +169,14 @@ class Server:
         ga = (C.c_void_p * K)(*[g.data_ptr() for g in grads])
         _check(load().dcasgd_push_batch(self._h, wa, ga, K, _stream_ptr(stream)),
                "dcasgd_push_batch")
+
+    def push_synth(self, worker: int, hdiag, wstar, sigma: float, seed: int, stream=None) -> None:
+        """Synthetic worker fused into the push: the gradient of worker's snapshot is
+        formed in registers (noise keyed by the server's push counter) and applied."""
+        assert hdiag.is_cuda and wstar.is_cuda and hdiag.numel() == wstar.numel() == self.d
+        _check(load().dcasgd_push_synth(self._h, int(worker), hdiag.data_ptr(), wstar.data_ptr(),
+                                        float(sigma), int(seed), _stream_ptr(stream)),
+               "dcasgd_push_synth")
 
     def sync_fold(self, grads: Sequence, eta_hat: float, stream=None) -> None:
         """Fold J same-snapshot gradients into w (the supplement's synchronous variant)."""

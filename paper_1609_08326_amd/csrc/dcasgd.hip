@@ -274,6 +274,44 @@ int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads, 
     return launched(h);
 }
 
+int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* wstar, float sigma,
+                      uint64_t seed, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (worker < 0 || worker >= h->M || !hdiag || !wstar || !std::isfinite(sigma))
+        return fail(h, DCASGD_EINVAL);
+    if (h->d > ((size_t)1 << 34) || h->t > 0xFFFFFFFFull) return fail(h, DCASGD_EINVAL);
+    if (!aligned(hdiag, 16) || !aligned(wstar, 16)) return fail(h, DCASGD_EALIGN);
+    const size_t vb = h->d * 4, bb = (size_t)h->M * h->bak_stride * 4;
+    const void* loss[2] = {hdiag, wstar};
+    for (const void* p : loss)
+        if (overlaps(p, vb, h->w, vb) || overlaps(p, vb, h->bak, bb) ||
+            (h->ms && overlaps(p, vb, h->ms, vb)))
+            return fail(h, DCASGD_EINVAL);
+    const size_t n4 = h->d / 4;
+    float* row = h->bak + (size_t)worker * h->bak_stride;
+    const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint32_t push_idx = (uint32_t)h->t;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    with_bool(h->adaptive, [&](auto AD) {
+      with_bool(h->grad_bf16, [&](auto BF) {
+        with_bool(h->pull_on_push, [&](auto PL) {
+          with_items(h->items, [&](auto IT) {
+              hipLaunchKernelGGL((push_synth_kernel<decltype(AD)::value, decltype(BF)::value,
+                                                    decltype(PL)::value, decltype(IT)::value>),
+                                 dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row, hdiag,
+                                 wstar, sigma, k0, k1, push_idx, n4, h->d);
+          });
+        });
+      });
+    });
+    h->stream = s;
+    h->t += 1;
+    if (h->pull_on_push) h->fresh_at[(size_t)worker] = h->t;
+    return launched(h);
+}
+
 int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream) {
     if (!h) return DCASGD_EINVAL;
     if (!h->ready) return fail(h, DCASGD_ESTATE);

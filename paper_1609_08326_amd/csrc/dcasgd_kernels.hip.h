@@ -544,4 +544,91 @@ synth_grad_kernel(const float* __restrict__ snap, const float* __restrict__ hdia
     }
 }
 
+// ---- synthetic worker fused into the push (and the pusher's pull) ----------------
+// For the synthetic workload the arriving gradient is a function of the
+// pusher's own backup, which the push reads anyway: compute it in registers
+// instead of writing it to HBM and reading it back.  Per parameter: read
+// backup, h, wstar, w, MeanSquare (20 B), write w, MeanSquare, backup (12 B).
+// The arithmetic is the worker kernel's followed by the push kernel's, so the
+// results are the same bits as the two separate launches.
+template <bool BF16>
+__device__ __forceinline__ float synth_delivered(float snap, float h, float wstar, float sigma,
+                                                 float z) {
+    const float g = synth_one(snap, h, wstar, sigma, z);
+    if constexpr (BF16) return widen_bf16(narrow_bf16(g));
+    else return g;
+}
+
+template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, bool CHECKED>
+__device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restrict__ w,
+                                                float* __restrict__ ms, float* __restrict__ bak,
+                                                const float* __restrict__ hdiag,
+                                                const float* __restrict__ wstar, float sigma,
+                                                uint32_t k0, uint32_t k1, uint32_t t,
+                                                size_t first, size_t n4) {
+    f32x4 W[ITEMS], B[ITEMS], H[ITEMS], O[ITEMS], S[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const size_t q = first + (size_t)j * blockDim.x;
+        if (!CHECKED || q < n4) {
+            B[j] = load4<true>(bak, q);
+            H[j] = load4<true>(hdiag, q);
+            O[j] = load4<true>(wstar, q);
+            W[j] = load4<true>(w, q);
+            if constexpr (ADAPTIVE) S[j] = load4<true>(ms, q);
+            else S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        } else {
+            B[j] = H[j] = O[j] = W[j] = S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const size_t q = first + (size_t)j * blockDim.x;
+        if (!CHECKED || q < n4) {
+            const f32x4 z = normals_for_quad(k0, k1, t, (uint32_t)q);
+            f32x4 g;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                g[c] = synth_delivered<BF16>(B[j][c], H[j][c], O[j][c], sigma, z[c]);
+            apply_push4<ADAPTIVE>(hp, g, B[j], W[j], S[j]);
+            store4<true>(w, q, W[j]);
+            if constexpr (ADAPTIVE) store4<true>(ms, q, S[j]);
+            if constexpr (PULL) store4<true>(bak, q, W[j]);
+        }
+    }
+}
+
+template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS>
+__global__ void __launch_bounds__(512)
+push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
+                  float* __restrict__ bak, const float* __restrict__ hdiag,
+                  const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
+                  uint32_t t, size_t n4, size_t d) {
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t first = tile * tile_quads + threadIdx.x;
+        if ((tile + 1) * tile_quads <= n4)
+            push_synth_tile<ADAPTIVE, BF16, PULL, ITEMS, false>(hp, w, ms, bak, hdiag, wstar, sigma,
+                                                                k0, k1, t, first, n4);
+        else
+            push_synth_tile<ADAPTIVE, BF16, PULL, ITEMS, true>(hp, w, ms, bak, hdiag, wstar, sigma,
+                                                               k0, k1, t, first, n4);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && 4 * n4 < d) {
+        const f32x4 z = normals_for_quad(k0, k1, t, (uint32_t)n4);
+        for (size_t i = 4 * n4; i < d; ++i) {
+            const float b = bak[i];
+            const float g = synth_delivered<BF16>(b, hdiag[i], wstar[i], sigma, z[i - 4 * n4]);
+            float wi = w[i];
+            float si = 0.f;
+            if constexpr (ADAPTIVE) si = ms[i];
+            apply_push<ADAPTIVE>(hp, g, b, wi, si);
+            w[i] = wi;
+            if constexpr (ADAPTIVE) ms[i] = si;
+            if constexpr (PULL) bak[i] = wi;
+        }
+    }
+}
+
 }  // namespace dcasgd

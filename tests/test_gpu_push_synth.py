@@ -1,0 +1,83 @@
+"""GPU parity for the worker+push fusion (synthetic workload only): the fused
+launch must leave the same bits as the oracle's event loop, which is also
+what the separate worker and push launches produce."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1609_08326_amd import workloads as W
+
+from gpu_harness import GpuRun, assert_same_bits, oracle_run
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_fused(wl, fused_pull=True, launch=None):
+    import torch
+    from paper_1609_08326_amd import binding as B
+    hd_h, ws_h, order = wl.hdiag(), wl.wstar(), wl.arrivals()
+    hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
+                  wl.eps, grad_bf16=wl.grad_bf16, pull_on_push=fused_pull)
+    if launch:
+        sv.set_launch(**launch)
+    for m in order:
+        sv.push_synth(int(m), hd, ws, wl.sigma, wl.seed)
+        if not fused_pull:
+            sv.pull(int(m))
+    torch.cuda.synchronize()
+    assert sv.t == len(order)
+    return sv, hd_h, ws_h, order
+
+
+def check(sv, ref, wl, idx=None):
+    sel = (lambda a: a) if idx is None else (lambda a: a[idx.astype(np.int64)])
+    assert_same_bits(sel(sv.w.cpu().numpy()), ref.w(), "w")
+    if sv.ms is not None:
+        assert_same_bits(sel(sv.ms.cpu().numpy()), ref.ms(), "ms")
+    bak = sv.bak[:, : wl.d].cpu().numpy()
+    for m in range(wl.M):
+        assert_same_bits(sel(bak[m]), ref.bak(m), "bak[%d]" % m)
+
+
+@pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_push_synth_small_sizes(mode, bf16):
+    for d in (1, 3, 4, 6, 1023, 2048 + 1, 50001):
+        for fused_pull, launch in ((True, None), (False, dict(threads=64, items=4)),
+                                   (True, dict(threads=512, items=1, max_blocks=2))):
+            wl = W.Workload("small", d=d, M=3, T=20, mode=mode, eta=0.1,
+                            lambda0=2.0 if mode == W.MODE_A else 0.04, ema_m=0.95, eps=1e-7,
+                            h_lo=1e-3, h_hi=1.0, wstar_sigma=1.0, sigma=0.01, order="iid",
+                            grad_bf16=bf16, seed=91)
+            say("push_synth d=%d mode=%d bf16=%s pull=%s launch=%s" % (d, mode, bf16, fused_pull, launch))
+            sv, hd_h, ws_h, order = run_fused(wl, fused_pull, launch)
+            ref = oracle_run(wl, hd_h, ws_h, order, nthreads=1)
+            check(sv, ref, wl)
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_push_synth_full_size_sampled(cfg):
+    wl = W.CONFIGS[cfg]
+    if cfg == 4:
+        wl = wl.replace(T=24)
+    say("push_synth full size %s" % wl.name)
+    sv, hd_h, ws_h, order = run_fused(wl)
+    idx = wl.sample_indices(100_000, edge=4096)
+    ref = oracle_run(wl, hd_h, ws_h, order, idx=idx, nthreads=16)
+    check(sv, ref, wl, idx=idx)
+
+
+def test_push_synth_equals_separate_launches():
+    wl = W.CONFIGS[1].replace(T=60)
+    sv, _, _, _ = run_fused(wl)
+    plain = GpuRun(wl)
+    assert_same_bits(sv.w.cpu().numpy(), plain.w, "fused vs separate w")
+    assert_same_bits(sv.ms.cpu().numpy(), plain.ms, "fused vs separate ms")
+    assert_same_bits(sv.bak[:, : wl.d].cpu().numpy().ravel(), plain.bak.ravel(), "fused vs separate bak")
