@@ -139,6 +139,13 @@ int dcasgd_last_error(dcasgd_t h);
 const char* dcasgd_strerror(int code);
 
 /*
+ * Change the learning rate for all later pushes (the experiments of Section 6
+ * divide it by ten at fixed epochs).  Pushes already enqueued keep the value
+ * they were launched with.  eta must be finite.
+ */
+int dcasgd_set_eta(dcasgd_t h, float eta);
+
+/*
  * Launch shape used by this handle's kernels.  threads: 64..512, a multiple
  * of 64; items: float4 groups per thread, one of 1, 2, 4; max_blocks: 0 = one
  * block per tile, otherwise blocks loop over tiles; streaming: 0 = plain

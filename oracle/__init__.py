@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
         L.oracle_destroy.restype = None
         L.oracle_step.argtypes = [vp]
         L.oracle_step.restype = C.c_uint64
+        L.oracle_set_eta.argtypes = [vp, C.c_float]
+        L.oracle_set_eta.restype = None
         L.oracle_push.argtypes = [vp, C.c_int, f32p]
         L.oracle_push.restype = C.c_int
         L.oracle_pull.argtypes = [vp, C.c_int]
@@ -158,6 +160,9 @@ class Server:
     @property
     def t(self) -> int:
         return int(lib().oracle_step(self._h))
+
+    def set_eta(self, eta: float) -> None:
+        lib().oracle_set_eta(self._h, float(eta))
 
     def push(self, worker: int, g) -> None:
         g = _f32(g).ravel()

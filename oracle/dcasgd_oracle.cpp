@@ -339,6 +339,9 @@ void oracle_destroy(void* h) { delete static_cast<Server*>(h); }
 
 uint64_t oracle_step(void* h) { return static_cast<Server*>(h)->t; }
 
+// Learning-rate schedule (Section 6 divides eta by ten at fixed epochs).
+void oracle_set_eta(void* h, float eta) { static_cast<Server*>(h)->eta = eta; }
+
 // Algorithm 2 "receive g_m": g has n floats (already widened if it travelled
 // as bf16).
 int oracle_push(void* h, int worker, const float* g) {

@@ -40,6 +40,7 @@ _PROTOTYPES = {
     "dcasgd_step": (C.c_uint64, [C.c_void_p]),
     "dcasgd_last_error": (C.c_int, [C.c_void_p]),
     "dcasgd_strerror": (C.c_char_p, [C.c_int]),
+    "dcasgd_set_eta": (C.c_int, [C.c_void_p, C.c_float]),
     "dcasgd_set_launch": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]),
     "dcasgd_synth_grad": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_uint64,
                                     C.c_uint32, C.c_void_p, C.c_int, C.c_size_t, C.c_void_p,
@@ -149,6 +150,10 @@ class Server:
     @property
     def t(self) -> int:
         return int(load().dcasgd_step(self._h))
+
+    def set_eta(self, eta: float) -> None:
+        """Learning rate of all later pushes (step schedules)."""
+        _check(load().dcasgd_set_eta(self._h, float(eta)), "dcasgd_set_eta")
 
     def set_launch(self, threads: int = 0, items: int = 0, max_blocks: int = 0,
                    streaming: int = 2) -> None:

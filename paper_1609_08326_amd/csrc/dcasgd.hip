@@ -370,6 +370,13 @@ const char* dcasgd_strerror(int code) {
     }
 }
 
+int dcasgd_set_eta(dcasgd_t h, float eta) {
+    if (!h) return DCASGD_EINVAL;
+    if (!std::isfinite(eta)) return fail(h, DCASGD_EINVAL);
+    h->hp.eta = eta;       // passed by value with every launch: later pushes use it
+    return DCASGD_OK;
+}
+
 int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming) {
     if (!h) return DCASGD_EINVAL;
     if (threads > 0 && !valid_threads(threads)) return fail(h, DCASGD_EINVAL);

@@ -167,3 +167,25 @@ def test_rejected_calls_launch_nothing():
     torch.cuda.synchronize()
     assert sv.t == 0
     assert float(sv.w.abs().max()) == 0.0
+
+
+def test_learning_rate_schedule_matches_oracle():
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = small(30011, M=4, T=30)
+    hd_h, ws_h, order = wl.hdiag(), wl.wstar(), wl.arrivals()
+    hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
+                  wl.eps, pull_on_push=True)
+    ref = oracle.Server(wl.w0(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+    g = torch.empty(wl.d, device="cuda")
+    for t, m in enumerate(order):
+        if t in (10, 20):
+            sv.set_eta(wl.eta * 0.1 ** (t // 10))
+            ref.set_eta(wl.eta * 0.1 ** (t // 10))
+        B.synth_grad(sv.snapshot(int(m)), hd, ws, wl.sigma, wl.seed, t, g)
+        sv.push(int(m), g)
+        ref.run(order[t:t + 1], hd_h, ws_h, wl.sigma, wl.seed)
+    torch.cuda.synchronize()
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "scheduled w")
+    assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "scheduled ms")

@@ -368,3 +368,20 @@ def test_compensation_helps_on_the_quadratic():
         dw = sv.w().astype(np.float64) - wstar
         loss[lam] = 0.5 * float(np.sum(h * dw * dw))
     assert loss[0.04] <= loss[0.0]
+
+
+def test_set_eta_changes_later_pushes_only():
+    """A step schedule (Section 6 divides the learning rate by ten at fixed epochs):
+    with one worker and zero delay the run is SGD with the scheduled rates."""
+    rng = np.random.default_rng(31)
+    n = 50
+    w0 = rng.standard_normal(n).astype(F32)
+    sv = oracle.Server(w0, 1, 0.5, 0.04, MODE_C)
+    w = w0.copy()
+    for step, eta in enumerate([0.5, 0.5, 0.05, 0.05, 0.005]):
+        sv.set_eta(eta)
+        g = rng.standard_normal(n).astype(F32)
+        sv.pull(0)
+        sv.push(0, g)
+        w = (w - (F32(eta) * g).astype(F32)).astype(F32)
+        assert np.array_equal(sv.w(), w), step
