@@ -88,3 +88,25 @@ def test_workloads_are_deterministic_and_shaped():
     assert all(sorted(r) == list(range(16)) for r in q.tolist())
     idx = W.CONFIGS[2].sample_indices(1000, edge=64)
     assert idx[0] == 0 and idx[-1] == W.CONFIGS[2].d - 1 and (idx[1:] > idx[:-1]).all()
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """There is no fallback path: without the built library the binding raises."""
+    from paper_1609_08326_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libdcasgd.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load()
+    with pytest.raises(FileNotFoundError):
+        binding.strerror(0)
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The oracle is test infrastructure; nothing under the package may reach for it."""
+    pkg = os.path.join(ROOT, "paper_1609_08326_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "dcasgd_oracle" not in text, f
