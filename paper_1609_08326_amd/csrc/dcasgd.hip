@@ -183,6 +183,8 @@ dcasgd_t dcasgd_create(size_t d, int M, float eta, float lambda0, int mode, floa
     h->hp.ema_m = ema_m;
     h->hp.one_minus_m = 1.0f - ema_m;
     h->hp.eps = eps;
+    const float mag = std::fabs(lambda0);
+    h->hp.lambda_midrange = (mag >= 0x1p-40f && mag <= 0x1p40f) ? 1 : 0;
     h->adaptive = variant == DCASGD_MODE_A;
     h->grad_bf16 = (flags & DCASGD_GRAD_BF16) != 0;
     h->pull_on_push = (flags & DCASGD_PULL_ON_PUSH) != 0;
