@@ -38,5 +38,24 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+PROBE_SRC = os.path.join(CSRC, "membw_probe.hip")
+PROBE = os.path.join(_PKG, "membw_probe")
+
+
+def build_probe(force: bool = True, verbose: bool = False) -> str:
+    """Build the stand-alone memory-system probe (an executable, not part of the library)."""
+    stale = (not os.path.exists(PROBE)) or os.path.getmtime(PROBE) < os.path.getmtime(PROBE_SRC)
+    if force or stale:
+        tmp = PROBE + ".tmp.%d" % os.getpid()
+        cmd = [HIPCC, "--offload-arch=gfx950", "-std=c++17", "-O3",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", PROBE_SRC, "-o", tmp]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        os.replace(tmp, PROBE)
+    return PROBE
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))
+    print(build_probe(force=True, verbose=True))
