@@ -63,6 +63,10 @@ def lib() -> C.CDLL:
         L.oracle_destroy.restype = None
         L.oracle_step.argtypes = [vp]
         L.oracle_step.restype = C.c_uint64
+        L.oracle_set_momentum.argtypes = [vp, C.c_float]
+        L.oracle_set_momentum.restype = None
+        L.oracle_get_vel.argtypes = [vp, f32p]
+        L.oracle_get_vel.restype = None
         L.oracle_set_eta.argtypes = [vp, C.c_float]
         L.oracle_set_eta.restype = None
         L.oracle_push.argtypes = [vp, C.c_int, f32p]
@@ -163,6 +167,16 @@ class Server:
 
     def set_eta(self, eta: float) -> None:
         lib().oracle_set_eta(self._h, float(eta))
+
+    def set_momentum(self, mu: float) -> None:
+        """Heavy-ball momentum on the compensated gradient; the velocity restarts at zero."""
+        lib().oracle_set_momentum(self._h, float(mu))
+        self._mu = float(mu)
+
+    def vel(self) -> np.ndarray:
+        out = np.zeros(self.n, dtype=np.float32)
+        lib().oracle_get_vel(self._h, _fp(out))
+        return out
 
     def push(self, worker: int, g) -> None:
         g = _f32(g).ravel()

@@ -41,6 +41,11 @@
 //     (the supplement only suggests ordering by distance from w_t); lambda
 //     may be the adaptive one, MeanSquare then advances once per gradient;
 //     eta_hat/J is formed once in binary32.
+//   * momentum: the paper names momentum variants (footnote, Section 6)
+//     without a formula.  Implemented as a proposal, the classical heavy
+//     ball on the compensated gradient: v <- mu*v + g_dc, w <- w - eta*v, one
+//     velocity vector per server.  The pins fix that this rule is what is
+//     computed; whether it is the authors' rule is unpinned.
 //
 // Pins (see tests/test_oracle_*.py): lambda = 0 gives ASGD (Eq. 2.2); M = 1
 // gives sequential SGD; exact-rational hand trace; closed forms for a
@@ -177,24 +182,26 @@ struct Server {
     float eta = 0, lambda0 = 0;
     int adaptive = 0;      // 0: DC-ASGD-c, 1: DC-ASGD-a
     float ema_m = 0, one_minus_m = 0, eps = 0;
+    int momentum = 0;      // 1: heavy-ball momentum on the compensated gradient
+    float mu = 0;
     uint64_t t = 0;        // pushes applied so far
-    std::vector<float> w, ms;
+    std::vector<float> w, ms, vel;
     std::vector<std::vector<float>> bak;
 };
 
-// Eq. 4.1 with lambda_t = lambda_0, one element.
-inline void push_elem_const(const Server& sv, float g, float b, float* w) {
-    const float diff = *w - b;
+// The delay-compensated gradient of Eq. 4.1 with lambda_t = lambda_0, one element.
+inline float compensated_const(const Server& sv, float g, float b, float w) {
+    const float diff = w - b;
     const float g2 = g * g;
     const float c1 = sv.lambda0 * g2;
     const float c2 = c1 * diff;
-    const float gd = g + c2;            // delay-compensated gradient
-    const float st = sv.eta * gd;
-    *w = *w - st;
+    const float gd = g + c2;
+    return gd;
 }
 
-// Eq. 18 followed by Eq. 4.1 with lambda_t = lambda_0 / sqrt(MeanSquare + eps).
-inline void push_elem_adaptive(const Server& sv, float g, float b, float* w, float* ms) {
+// Eq. 18, then the delay-compensated gradient with
+// lambda_t = lambda_0 / sqrt(MeanSquare + eps).
+inline float compensated_adaptive(const Server& sv, float g, float b, float w, float* ms) {
     const float g2 = g * g;
     const float t1 = sv.ema_m * *ms;
     const float t2 = sv.one_minus_m * g2;
@@ -202,21 +209,35 @@ inline void push_elem_adaptive(const Server& sv, float g, float b, float* w, flo
     const float den = *ms + sv.eps;
     const float rt = std::sqrt(den);
     const float lam = sv.lambda0 / rt;
-    const float diff = *w - b;
+    const float diff = w - b;
     const float c1 = lam * g2;
     const float c2 = c1 * diff;
     const float gd = g + c2;
-    const float st = sv.eta * gd;
-    *w = *w - st;
+    return gd;
+}
+
+// One arriving gradient element: w <- w - eta * gd (Algorithm 2), or, with
+// momentum (the paper only mentions momentum variants in a footnote of
+// Section 6; the rule here is the classical heavy ball applied to the
+// compensated gradient): v <- mu*v + gd; w <- w - eta*v.
+inline void push_elem(Server& sv, float eta, float g, float b, size_t i) {
+    const float gd = sv.adaptive ? compensated_adaptive(sv, g, b, sv.w[i], &sv.ms[i])
+                                 : compensated_const(sv, g, b, sv.w[i]);
+    if (sv.momentum) {
+        const float mv = sv.mu * sv.vel[i];
+        sv.vel[i] = mv + gd;
+        const float st = eta * sv.vel[i];
+        sv.w[i] = sv.w[i] - st;
+    } else {
+        const float st = eta * gd;
+        sv.w[i] = sv.w[i] - st;
+    }
 }
 
 // Algorithm 2, "receive g_m", elements [lo, hi). g is indexed like w.
 void push_range(Server& sv, int m, const float* g, size_t lo, size_t hi) {
     const float* b = sv.bak[m].data();
-    for (size_t i = lo; i < hi; ++i) {
-        if (sv.adaptive) push_elem_adaptive(sv, g[i], b[i], &sv.w[i], &sv.ms[i]);
-        else             push_elem_const(sv, g[i], b[i], &sv.w[i]);
-    }
+    for (size_t i = lo; i < hi; ++i) push_elem(sv, sv.eta, g[i], b[i], i);
 }
 
 // Algorithm 2, "pull request": w_bak(m) <- w_t, elements [lo, hi).
@@ -230,18 +251,10 @@ void pull_range(Server& sv, int m, size_t lo, size_t hi) {
 // This is the push rule with the learning rate eta_hat/J and with w_t in the
 // role of the backup for every j.
 void sync_fold(Server& sv, const float* const* g, int J, float eta_hat) {
-    Server step_rule = Server();            // same hyper-parameters, other learning rate
-    step_rule.lambda0 = sv.lambda0;
-    step_rule.ema_m = sv.ema_m;
-    step_rule.one_minus_m = sv.one_minus_m;
-    step_rule.eps = sv.eps;
-    step_rule.eta = eta_hat / (float)J;
+    const float step = eta_hat / (float)J;  // per-gradient learning rate
     for (size_t i = 0; i < sv.n; ++i) {
         const float anchor = sv.w[i];       // w_t
-        for (int j = 0; j < J; ++j) {
-            if (sv.adaptive) push_elem_adaptive(step_rule, g[j][i], anchor, &sv.w[i], &sv.ms[i]);
-            else             push_elem_const(step_rule, g[j][i], anchor, &sv.w[i]);
-        }
+        for (int j = 0; j < J; ++j) push_elem(sv, step, g[j][i], anchor, i);
     }
 }
 
@@ -338,6 +351,18 @@ void* oracle_create(size_t n, int M, float eta, float lambda0, int mode,
 void oracle_destroy(void* h) { delete static_cast<Server*>(h); }
 
 uint64_t oracle_step(void* h) { return static_cast<Server*>(h)->t; }
+
+// Switch heavy-ball momentum on (velocity restarts at zero) or off (mu == 0).
+void oracle_set_momentum(void* h, float mu) {
+    Server& sv = *static_cast<Server*>(h);
+    sv.mu = mu;
+    sv.momentum = mu != 0.0f;
+    sv.vel.assign(sv.momentum ? sv.n : 0, 0.0f);
+}
+void oracle_get_vel(void* h, float* out) {
+    Server& sv = *static_cast<Server*>(h);
+    if (sv.momentum) std::memcpy(out, sv.vel.data(), sv.n * sizeof(float));
+}
 
 // Learning-rate schedule (Section 6 divides eta by ten at fixed epochs).
 void oracle_set_eta(void* h, float eta) { static_cast<Server*>(h)->eta = eta; }
