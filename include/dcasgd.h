@@ -139,6 +139,19 @@ int dcasgd_last_error(dcasgd_t h);
 const char* dcasgd_strerror(int code);
 
 /*
+ * Momentum variant.  Section 6 mentions momentum variants in a footnote and
+ * gives no formula; this is the classical heavy ball applied to the
+ * delay-compensated gradient g_dc of Eq. 4.1, one velocity per server:
+ *   mv = mu*v; v = mv+g_dc; st = eta*v; w = w-st
+ * It applies to every later dcasgd_push, dcasgd_push_batch, dcasgd_push_synth
+ * and dcasgd_sync_fold.  vel: device pointer, d floats, 16-byte aligned, not
+ * overlapping the bound state, owned by the caller; it is zeroed on stream.
+ * mu == 0 or vel == NULL switches back to the plain update.  Needs
+ * dcasgd_bind first.
+ */
+int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream);
+
+/*
  * Change the learning rate for all later pushes (the experiments of Section 6
  * divide it by ten at fixed epochs).  Pushes already enqueued keep the value
  * they were launched with.  eta must be finite.

@@ -40,6 +40,7 @@ _PROTOTYPES = {
     "dcasgd_step": (C.c_uint64, [C.c_void_p]),
     "dcasgd_last_error": (C.c_int, [C.c_void_p]),
     "dcasgd_strerror": (C.c_char_p, [C.c_int]),
+    "dcasgd_set_momentum": (C.c_int, [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]),
     "dcasgd_set_eta": (C.c_int, [C.c_void_p, C.c_float]),
     "dcasgd_set_launch": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]),
     "dcasgd_synth_grad": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_uint64,
@@ -150,6 +151,19 @@ class Server:
     @property
     def t(self) -> int:
         return int(load().dcasgd_step(self._h))
+
+    def set_momentum(self, mu: float, stream=None) -> None:
+        """Heavy-ball momentum on the compensated gradient for all later pushes; the
+        velocity (``self.vel``, torch-owned) restarts at zero.  mu = 0 switches it off."""
+        import torch
+        if mu == 0.0:
+            self.vel = None
+            _check(load().dcasgd_set_momentum(self._h, 0.0, None, _stream_ptr(stream)),
+                   "dcasgd_set_momentum")
+            return
+        self.vel = torch.empty(self.d, dtype=torch.float32, device=self.w.device)
+        _check(load().dcasgd_set_momentum(self._h, float(mu), self.vel.data_ptr(),
+                                          _stream_ptr(stream)), "dcasgd_set_momentum")
 
     def set_eta(self, eta: float) -> None:
         """Learning rate of all later pushes (step schedules)."""

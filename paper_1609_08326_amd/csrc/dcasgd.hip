@@ -372,6 +372,31 @@ const char* dcasgd_strerror(int code) {
     }
 }
 
+int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->bound) return fail(h, DCASGD_ESTATE);
+    if (!std::isfinite(mu)) return fail(h, DCASGD_EINVAL);
+    if (mu == 0.0f || !vel) {                 // plain update again
+        h->hp.mu = 0.0f;
+        h->hp.vel = nullptr;
+        return DCASGD_OK;
+    }
+    if (!aligned(vel, 16)) return fail(h, DCASGD_EALIGN);
+    const size_t vb = h->d * 4;
+    if (overlaps(vel, vb, h->w, vb) ||
+        overlaps(vel, vb, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+        (h->ms && overlaps(vel, vb, h->ms, vb)))
+        return fail(h, DCASGD_EINVAL);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t n4 = h->d / 4;
+    hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n4, 512, 4096)), dim3(512), 0, s, vel, 0.0f, n4,
+                       h->d);
+    h->hp.mu = mu;
+    h->hp.vel = vel;
+    h->stream = s;
+    return launched(h);
+}
+
 int dcasgd_set_eta(dcasgd_t h, float eta) {
     if (!h) return DCASGD_EINVAL;
     if (!std::isfinite(eta)) return fail(h, DCASGD_EINVAL);

@@ -29,6 +29,8 @@ struct Hyper {
     float one_minus_m;   // 1 - m, formed once on the host in binary32
     float eps;
     int lambda_midrange; // |lambda0| in [2^-40, 2^40]: the short sqrt/divide may be used
+    float mu;            // momentum coefficient (used only when vel is set)
+    float* vel;          // velocity vector, or nullptr: plain update
 };
 
 // ---- memory helpers ---------------------------------------------------------
@@ -79,12 +81,33 @@ __device__ __forceinline__ float load_grad1(const void* grad, size_t i) {
     else return reinterpret_cast<const float*>(grad)[i];
 }
 
+// Velocity of a float4 group (zeros when momentum is off; the branch is uniform).
+__device__ __forceinline__ f32x4 load_vel4(const Hyper& hp, size_t quad) {
+    if (hp.vel) return load4<true>(hp.vel, quad);
+    return f32x4{0.f, 0.f, 0.f, 0.f};
+}
+__device__ __forceinline__ void store_vel4(const Hyper& hp, size_t quad, f32x4 v) {
+    if (hp.vel) store4<true>(hp.vel, quad, v);
+}
+
+// w <- w - eta*gdc, or with momentum v <- mu*v + gdc; w <- w - eta*v.
+__device__ __forceinline__ void take_step(const Hyper& hp, float gdc, float& w, float& v) {
+    float dir = gdc;
+    if (hp.vel) {
+        const float carried = hp.mu * v;
+        v = carried + gdc;
+        dir = v;
+    }
+    const float step = hp.eta * dir;
+    w = w - step;
+}
+
 // ---- the update rule ----------------------------------------------------------
 // Eq. 4.1 applied to one parameter; in the adaptive variant Eq. 18 refreshes
 // MeanSquare first and lambda is lambda0 / sqrt(MeanSquare + eps).
 template <bool ADAPTIVE>
 __device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
-                                           float& w, float& ms) {
+                                           float& w, float& ms, float& v) {
     const float gsq = g * g;
     float lam = hp.lambda0;
     if constexpr (ADAPTIVE) {
@@ -99,8 +122,7 @@ __device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
     const float curv = lam * gsq;         // diagonal Hessian estimate
     const float comp = curv * drift;
     const float gdc = g + comp;           // delay-compensated gradient
-    const float step = hp.eta * gdc;
-    w = w - step;
+    take_step(hp, gdc, w, v);
 }
 
 // Correctly rounded square root and quotient without the exponent rescaling and
@@ -142,13 +164,14 @@ __device__ __forceinline__ bool in_midrange(float x) {
 // are used, otherwise the general ones: the result is the same bits either way.
 template <bool ADAPTIVE>
 __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, const f32x4& b,
-                                            f32x4& w, f32x4& ms) {
+                                            f32x4& w, f32x4& ms, f32x4& v) {
     if constexpr (!ADAPTIVE) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            float wc = w[c], mc = ms[c];
-            apply_push<false>(hp, g[c], b[c], wc, mc);
+            float wc = w[c], mc = ms[c], vc = v[c];
+            apply_push<false>(hp, g[c], b[c], wc, mc, vc);
             w[c] = wc;
+            v[c] = vc;
         }
     } else {
         float gsq[4], under[4], lam[4];
@@ -176,8 +199,10 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
             const float curv = lam[c] * gsq[c];
             const float comp = curv * drift;
             const float gdc = g[c] + comp;
-            const float step = hp.eta * gdc;
-            w[c] = w[c] - step;
+            float wc = w[c], vc = v[c];
+            take_step(hp, gdc, wc, vc);
+            w[c] = wc;
+            v[c] = vc;
         }
     }
 }
@@ -194,25 +219,27 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
                                           float* __restrict__ ms, float* __restrict__ bak,
                                           const void* __restrict__ grad, size_t first,
                                           size_t n4) {
-    f32x4 W[ITEMS], B[ITEMS], G[ITEMS], S[ITEMS];
+    f32x4 W[ITEMS], B[ITEMS], G[ITEMS], S[ITEMS], V[ITEMS];
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         const size_t q = first + (size_t)j * blockDim.x;
         if (!CHECKED || q < n4) {
+            V[j] = load_vel4(hp, q);
             G[j] = load_grad4<BF16, (NT >= 1)>(grad, q);
             B[j] = load4<(NT >= 1)>(bak, q);
             W[j] = load4<(NT >= 2)>(w, q);
             if constexpr (ADAPTIVE) S[j] = load4<(NT >= 2)>(ms, q);
             else S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         } else {
-            G[j] = B[j] = W[j] = S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            G[j] = B[j] = W[j] = S[j] = V[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         const size_t q = first + (size_t)j * blockDim.x;
-        apply_push4<ADAPTIVE>(hp, G[j], B[j], W[j], S[j]);
+        apply_push4<ADAPTIVE>(hp, G[j], B[j], W[j], S[j], V[j]);
         if (!CHECKED || q < n4) {
+            store_vel4(hp, q, V[j]);
             store4<(NT >= 2)>(w, q, W[j]);
             if constexpr (ADAPTIVE) store4<(NT >= 2)>(ms, q, S[j]);
             if constexpr (PULL) store4<(NT >= 1)>(bak, q, W[j]);
@@ -240,10 +267,12 @@ push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __re
             float wi = w[i];
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
-            apply_push<ADAPTIVE>(hp, load_grad1<BF16>(grad, i), bak[i], wi, si);
+            float vi = hp.vel ? hp.vel[i] : 0.f;
+            apply_push<ADAPTIVE>(hp, load_grad1<BF16>(grad, i), bak[i], wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
             if constexpr (PULL) bak[i] = wi;
+            if (hp.vel) hp.vel[i] = vi;
         }
     }
 }
@@ -280,6 +309,7 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
     f32x4 W = load4<false>(w, q);
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
+    f32x4 V = load_vel4(hp, q);
     const int full = (a.K / KC) * KC;     // entries covered by whole groups
     f32x4 G[KC], B[KC];
     if constexpr (PIPE) {
@@ -290,7 +320,7 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
             if (more) batch_load<BF16, KC, NT>(a, k0 + KC, q, Gn, Bn);
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
-                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S);
+                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S, V);
                 store4<NT>(a.bak[k0 + kk], q, W);
             }
             if (more) {
@@ -303,7 +333,7 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
             batch_load<BF16, KC, NT>(a, k0, q, G, B);
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
-                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S);
+                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S, V);
                 store4<NT>(a.bak[k0 + kk], q, W);
             }
         }
@@ -311,11 +341,12 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
     for (int k = full; k < a.K; ++k) {
         const f32x4 g = load_grad4<BF16, NT>(a.grad[k], q);
         const f32x4 b = load4<NT>(a.bak[k], q);
-        apply_push4<ADAPTIVE>(hp, g, b, W, S);
+        apply_push4<ADAPTIVE>(hp, g, b, W, S, V);
         store4<NT>(a.bak[k], q, W);
     }
     store4<false>(w, q, W);
     if constexpr (ADAPTIVE) store4<false>(ms, q, S);
+    store_vel4(hp, q, V);
 }
 
 template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool PIPE>
@@ -336,12 +367,14 @@ push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, Batch
             float wi = w[i];
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
+            float vi = hp.vel ? hp.vel[i] : 0.f;
             for (int k = 0; k < a.K; ++k) {
-                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[k], i), a.bak[k][i], wi, si);
+                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[k], i), a.bak[k][i], wi, si, vi);
                 a.bak[k][i] = wi;
             }
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
+            if (hp.vel) hp.vel[i] = vi;
         }
     }
 }
@@ -366,20 +399,22 @@ __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w
     f32x4 W = anchor;
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
+    f32x4 V = load_vel4(hp, q);
     const int full = (a.J / KC) * KC;
     for (int j0 = 0; j0 < full; j0 += KC) {
         f32x4 G[KC];
 #pragma unroll
         for (int jj = 0; jj < KC; ++jj) G[jj] = load_grad4<BF16, NT>(a.grad[j0 + jj], q);
 #pragma unroll
-        for (int jj = 0; jj < KC; ++jj) apply_push4<ADAPTIVE>(hp, G[jj], anchor, W, S);
+        for (int jj = 0; jj < KC; ++jj) apply_push4<ADAPTIVE>(hp, G[jj], anchor, W, S, V);
     }
     for (int j = full; j < a.J; ++j) {
         const f32x4 g = load_grad4<BF16, NT>(a.grad[j], q);
-        apply_push4<ADAPTIVE>(hp, g, anchor, W, S);
+        apply_push4<ADAPTIVE>(hp, g, anchor, W, S, V);
     }
     store4<false>(w, q, W);
     if constexpr (ADAPTIVE) store4<false>(ms, q, S);
+    store_vel4(hp, q, V);
 }
 
 template <bool ADAPTIVE, bool BF16, int KC, bool NT>
@@ -401,10 +436,12 @@ sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldAr
             float wi = anchor;
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
+            float vi = hp.vel ? hp.vel[i] : 0.f;
             for (int j = 0; j < a.J; ++j)
-                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[j], i), anchor, wi, si);
+                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[j], i), anchor, wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
+            if (hp.vel) hp.vel[i] = vi;
         }
     }
 }
@@ -634,11 +671,12 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
                                                 const float* __restrict__ wstar, float sigma,
                                                 uint32_t k0, uint32_t k1, uint32_t t,
                                                 size_t first, size_t n4) {
-    f32x4 W[ITEMS], B[ITEMS], H[ITEMS], O[ITEMS], S[ITEMS];
+    f32x4 W[ITEMS], B[ITEMS], H[ITEMS], O[ITEMS], S[ITEMS], V[ITEMS];
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         const size_t q = first + (size_t)j * blockDim.x;
         if (!CHECKED || q < n4) {
+            V[j] = load_vel4(hp, q);
             B[j] = load4<true>(bak, q);
             H[j] = load4<true>(hdiag, q);
             O[j] = load4<true>(wstar, q);
@@ -646,7 +684,7 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
             if constexpr (ADAPTIVE) S[j] = load4<true>(ms, q);
             else S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         } else {
-            B[j] = H[j] = O[j] = W[j] = S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            B[j] = H[j] = O[j] = W[j] = S[j] = V[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
 #pragma unroll
@@ -658,7 +696,8 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 g[c] = synth_delivered<BF16>(B[j][c], H[j][c], O[j][c], sigma, z[c]);
-            apply_push4<ADAPTIVE>(hp, g, B[j], W[j], S[j]);
+            apply_push4<ADAPTIVE>(hp, g, B[j], W[j], S[j], V[j]);
+            store_vel4(hp, q, V[j]);
             store4<true>(w, q, W[j]);
             if constexpr (ADAPTIVE) store4<true>(ms, q, S[j]);
             if constexpr (PULL) store4<true>(bak, q, W[j]);
@@ -691,10 +730,12 @@ push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
             float wi = w[i];
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
-            apply_push<ADAPTIVE>(hp, g, b, wi, si);
+            float vi = hp.vel ? hp.vel[i] : 0.f;
+            apply_push<ADAPTIVE>(hp, g, b, wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
             if constexpr (PULL) bak[i] = wi;
+            if (hp.vel) hp.vel[i] = vi;
         }
     }
 }

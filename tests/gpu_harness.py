@@ -27,7 +27,7 @@ class GpuRun:
     """State after running a workload through the HIP library."""
 
     def __init__(self, wl: W.Workload, *, fused: bool = True, batched: bool = False,
-                 launch: dict | None = None, synth_launch: tuple = (0, 0),
+                 launch: dict | None = None, synth_launch: tuple = (0, 0), momentum: float = 0.0,
                  hdiag=None, wstar=None, arrivals=None):
         import torch
         from paper_1609_08326_amd import binding as B
@@ -43,6 +43,8 @@ class GpuRun:
                       grad_bf16=wl.grad_bf16, pull_on_push=fused and not batched)
         if launch:
             sv.set_launch(**launch)
+        if momentum:
+            sv.set_momentum(momentum)
         gdt = torch.bfloat16 if wl.grad_bf16 else torch.float32
         K = wl.K if batched else 1
         gbuf = [torch.empty(wl.d, dtype=gdt, device=dev) for _ in range(K)]
@@ -80,14 +82,18 @@ class GpuRun:
         self.w = sv.w.cpu().numpy()
         self.ms = sv.ms.cpu().numpy() if sv.ms is not None else None
         self.bak = sv.bak[:, : wl.d].cpu().numpy()
+        self.vel = sv.vel.cpu().numpy() if getattr(sv, "vel", None) is not None else None
 
 
-def oracle_run(wl: W.Workload, hdiag, wstar, arrivals, idx=None, nthreads: int = 8):
+def oracle_run(wl: W.Workload, hdiag, wstar, arrivals, idx=None, nthreads: int = 8,
+               momentum: float = 0.0):
     """The oracle on the same inputs; idx selects a subset of elements."""
     w0 = wl.w0()
     if idx is not None:
         hdiag, wstar, w0 = hdiag[idx], wstar[idx], w0[idx]
     sv = oracle.Server(w0, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+    if momentum:
+        sv.set_momentum(momentum)
     sv.run(arrivals, hdiag, wstar, wl.sigma, wl.seed, gidx=idx, as_bf16=wl.grad_bf16,
            nthreads=nthreads)
     return sv
@@ -102,3 +108,5 @@ def compare(run: GpuRun, ref: "oracle.Server", idx=None, tag: str = "") -> None:
         assert_same_bits(sel(run.ms), ref.ms(), tag + " ms")
     for m in range(run.wl.M):
         assert_same_bits(sel(run.bak[m]), ref.bak(m), tag + " bak[%d]" % m)
+    if run.vel is not None:
+        assert_same_bits(sel(run.vel), ref.vel(), tag + " velocity")
