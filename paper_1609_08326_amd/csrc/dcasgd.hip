@@ -118,11 +118,12 @@ void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipSt
     float* row = h->bak + (size_t)worker * h->bak_stride;
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
     with_bool(h->adaptive, [&](auto AD) {
+     with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(fuse_pull, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
             with_level(h->streaming, [&](auto NT) {
-                hipLaunchKernelGGL((push_kernel<decltype(AD)::value, decltype(BF)::value,
+                hipLaunchKernelGGL((push_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value,
                                                 decltype(PL)::value, decltype(IT)::value,
                                                 decltype(NT)::value>),
                                    dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row,
@@ -131,6 +132,7 @@ void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipSt
           });
         });
       });
+     });
     });
 }
 
@@ -147,14 +149,16 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
     const int threads = h->batch_threads;
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
     with_bool(h->adaptive, [&](auto AD) {
+     with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(BF)::value,
+            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value,
                                                   DCASGD_BATCH_KC, decltype(NT)::value,
                                                   (DCASGD_BATCH_PIPE != 0)>),
                                dim3(grid), dim3(threads), 0, s, h->hp, h->w, h->ms, a, n4, h->d);
         });
       });
+     });
     });
 }
 
@@ -297,16 +301,18 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
     const uint32_t push_idx = (uint32_t)h->t;
     hipStream_t s = static_cast<hipStream_t>(stream);
     with_bool(h->adaptive, [&](auto AD) {
+     with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->pull_on_push, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
-              hipLaunchKernelGGL((push_synth_kernel<decltype(AD)::value, decltype(BF)::value,
+              hipLaunchKernelGGL((push_synth_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value,
                                                     decltype(PL)::value, decltype(IT)::value>),
                                  dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row, hdiag,
                                  wstar, sigma, k0, k1, push_idx, n4, h->d);
           });
         });
       });
+     });
     });
     h->stream = s;
     h->t += 1;
@@ -332,13 +338,15 @@ int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat,
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
     hipStream_t s = static_cast<hipStream_t>(stream);
     with_bool(h->adaptive, [&](auto AD) {
+     with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((sync_fold_kernel<decltype(AD)::value, decltype(BF)::value, 4,
+            hipLaunchKernelGGL((sync_fold_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value, 4,
                                                  decltype(NT)::value>),
                                dim3(grid), dim3(threads), 0, s, hp, h->w, h->ms, a, n4, h->d);
         });
       });
+     });
     });
     h->stream = s;
     h->t += (uint64_t)J;

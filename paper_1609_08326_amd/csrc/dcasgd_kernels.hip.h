@@ -81,19 +81,32 @@ __device__ __forceinline__ float load_grad1(const void* grad, size_t i) {
     else return reinterpret_cast<const float*>(grad)[i];
 }
 
-// Velocity of a float4 group (zeros when momentum is off; the branch is uniform).
+// Velocity of a float4 group.  MOM is a compile-time switch: the plain kernels
+// carry no velocity registers and no extra traffic.
+template <bool MOM>
 __device__ __forceinline__ f32x4 load_vel4(const Hyper& hp, size_t quad) {
-    if (hp.vel) return load4<true>(hp.vel, quad);
-    return f32x4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (MOM) return load4<true>(hp.vel, quad);
+    else return f32x4{0.f, 0.f, 0.f, 0.f};
 }
+template <bool MOM>
 __device__ __forceinline__ void store_vel4(const Hyper& hp, size_t quad, f32x4 v) {
-    if (hp.vel) store4<true>(hp.vel, quad, v);
+    if constexpr (MOM) store4<true>(hp.vel, quad, v);
+}
+template <bool MOM>
+__device__ __forceinline__ float load_vel1(const Hyper& hp, size_t i) {
+    if constexpr (MOM) return hp.vel[i];
+    else return 0.f;
+}
+template <bool MOM>
+__device__ __forceinline__ void store_vel1(const Hyper& hp, size_t i, float v) {
+    if constexpr (MOM) hp.vel[i] = v;
 }
 
 // w <- w - eta*gdc, or with momentum v <- mu*v + gdc; w <- w - eta*v.
+template <bool MOM>
 __device__ __forceinline__ void take_step(const Hyper& hp, float gdc, float& w, float& v) {
     float dir = gdc;
-    if (hp.vel) {
+    if constexpr (MOM) {
         const float carried = hp.mu * v;
         v = carried + gdc;
         dir = v;
@@ -105,7 +118,7 @@ __device__ __forceinline__ void take_step(const Hyper& hp, float gdc, float& w, 
 // ---- the update rule ----------------------------------------------------------
 // Eq. 4.1 applied to one parameter; in the adaptive variant Eq. 18 refreshes
 // MeanSquare first and lambda is lambda0 / sqrt(MeanSquare + eps).
-template <bool ADAPTIVE>
+template <bool ADAPTIVE, bool MOM>
 __device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
                                            float& w, float& ms, float& v) {
     const float gsq = g * g;
@@ -122,7 +135,7 @@ __device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
     const float curv = lam * gsq;         // diagonal Hessian estimate
     const float comp = curv * drift;
     const float gdc = g + comp;           // delay-compensated gradient
-    take_step(hp, gdc, w, v);
+    take_step<MOM>(hp, gdc, w, v);
 }
 
 // Correctly rounded square root and quotient without the exponent rescaling and
@@ -162,14 +175,14 @@ __device__ __forceinline__ bool in_midrange(float x) {
 // parameter; when every lane of the wave has all four radicands in the middle
 // of the exponent range (any realistic MeanSquare + eps) the short forms above
 // are used, otherwise the general ones: the result is the same bits either way.
-template <bool ADAPTIVE>
+template <bool ADAPTIVE, bool MOM>
 __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, const f32x4& b,
                                             f32x4& w, f32x4& ms, f32x4& v) {
     if constexpr (!ADAPTIVE) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             float wc = w[c], mc = ms[c], vc = v[c];
-            apply_push<false>(hp, g[c], b[c], wc, mc, vc);
+            apply_push<false, MOM>(hp, g[c], b[c], wc, mc, vc);
             w[c] = wc;
             v[c] = vc;
         }
@@ -200,7 +213,7 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
             const float comp = curv * drift;
             const float gdc = g[c] + comp;
             float wc = w[c], vc = v[c];
-            take_step(hp, gdc, wc, vc);
+            take_step<MOM>(hp, gdc, wc, vc);
             w[c] = wc;
             v[c] = vc;
         }
@@ -214,7 +227,7 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
 // NT: 0 = plain accesses, 1 = gradient and backup traffic non-temporal,
 // 2 = w and MeanSquare non-temporal as well (state too large to be re-read
 // from any cache before the next push).
-template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, int NT, bool CHECKED>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, int NT, bool CHECKED>
 __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w,
                                           float* __restrict__ ms, float* __restrict__ bak,
                                           const void* __restrict__ grad, size_t first,
@@ -224,7 +237,7 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
     for (int j = 0; j < ITEMS; ++j) {
         const size_t q = first + (size_t)j * blockDim.x;
         if (!CHECKED || q < n4) {
-            V[j] = load_vel4(hp, q);
+            V[j] = load_vel4<MOM>(hp, q);
             G[j] = load_grad4<BF16, (NT >= 1)>(grad, q);
             B[j] = load4<(NT >= 1)>(bak, q);
             W[j] = load4<(NT >= 2)>(w, q);
@@ -237,9 +250,9 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         const size_t q = first + (size_t)j * blockDim.x;
-        apply_push4<ADAPTIVE>(hp, G[j], B[j], W[j], S[j], V[j]);
+        apply_push4<ADAPTIVE, MOM>(hp, G[j], B[j], W[j], S[j], V[j]);
         if (!CHECKED || q < n4) {
-            store_vel4(hp, q, V[j]);
+            store_vel4<MOM>(hp, q, V[j]);
             store4<(NT >= 2)>(w, q, W[j]);
             if constexpr (ADAPTIVE) store4<(NT >= 2)>(ms, q, S[j]);
             if constexpr (PULL) store4<(NT >= 1)>(bak, q, W[j]);
@@ -247,7 +260,7 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
     }
 }
 
-template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, int NT>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, int NT>
 __global__ void __launch_bounds__(512)
 push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __restrict__ bak,
             const void* __restrict__ grad, size_t n4, size_t d) {
@@ -256,9 +269,9 @@ push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __re
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t first = tile * tile_quads + threadIdx.x;
         if ((tile + 1) * tile_quads <= n4)
-            push_tile<ADAPTIVE, BF16, PULL, ITEMS, NT, false>(hp, w, ms, bak, grad, first, n4);
+            push_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, NT, false>(hp, w, ms, bak, grad, first, n4);
         else
-            push_tile<ADAPTIVE, BF16, PULL, ITEMS, NT, true>(hp, w, ms, bak, grad, first, n4);
+            push_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, NT, true>(hp, w, ms, bak, grad, first, n4);
     }
     // up to three parameters beyond the last full group of four
     if (blockIdx.x == 0) {
@@ -267,12 +280,12 @@ push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __re
             float wi = w[i];
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
-            float vi = hp.vel ? hp.vel[i] : 0.f;
-            apply_push<ADAPTIVE>(hp, load_grad1<BF16>(grad, i), bak[i], wi, si, vi);
+            float vi = load_vel1<MOM>(hp, i);
+            apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(grad, i), bak[i], wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
             if constexpr (PULL) bak[i] = wi;
-            if (hp.vel) hp.vel[i] = vi;
+            store_vel1<MOM>(hp, i, vi);
         }
     }
 }
@@ -301,7 +314,7 @@ __device__ __forceinline__ void batch_load(const BatchArgs& a, int k0, size_t q,
     }
 }
 
-template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool PIPE, bool CHECKED>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool PIPE, bool CHECKED>
 __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ w,
                                            float* __restrict__ ms, const BatchArgs& a,
                                            size_t q, size_t n4) {
@@ -309,7 +322,7 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
     f32x4 W = load4<false>(w, q);
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
-    f32x4 V = load_vel4(hp, q);
+    f32x4 V = load_vel4<MOM>(hp, q);
     const int full = (a.K / KC) * KC;     // entries covered by whole groups
     f32x4 G[KC], B[KC];
     if constexpr (PIPE) {
@@ -320,7 +333,7 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
             if (more) batch_load<BF16, KC, NT>(a, k0 + KC, q, Gn, Bn);
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
-                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S, V);
+                apply_push4<ADAPTIVE, MOM>(hp, G[kk], B[kk], W, S, V);
                 store4<NT>(a.bak[k0 + kk], q, W);
             }
             if (more) {
@@ -333,7 +346,7 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
             batch_load<BF16, KC, NT>(a, k0, q, G, B);
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
-                apply_push4<ADAPTIVE>(hp, G[kk], B[kk], W, S, V);
+                apply_push4<ADAPTIVE, MOM>(hp, G[kk], B[kk], W, S, V);
                 store4<NT>(a.bak[k0 + kk], q, W);
             }
         }
@@ -341,15 +354,15 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
     for (int k = full; k < a.K; ++k) {
         const f32x4 g = load_grad4<BF16, NT>(a.grad[k], q);
         const f32x4 b = load4<NT>(a.bak[k], q);
-        apply_push4<ADAPTIVE>(hp, g, b, W, S, V);
+        apply_push4<ADAPTIVE, MOM>(hp, g, b, W, S, V);
         store4<NT>(a.bak[k], q, W);
     }
     store4<false>(w, q, W);
     if constexpr (ADAPTIVE) store4<false>(ms, q, S);
-    store_vel4(hp, q, V);
+    store_vel4<MOM>(hp, q, V);
 }
 
-template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool PIPE>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool PIPE>
 __global__ void __launch_bounds__(256)
 push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, BatchArgs a,
                   size_t n4, size_t d) {
@@ -357,9 +370,9 @@ push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, Batch
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t q = tile * blockDim.x + threadIdx.x;
         if ((tile + 1) * blockDim.x <= n4)
-            batch_quad<ADAPTIVE, BF16, KC, NT, PIPE, false>(hp, w, ms, a, q, n4);
+            batch_quad<ADAPTIVE, MOM, BF16, KC, NT, PIPE, false>(hp, w, ms, a, q, n4);
         else
-            batch_quad<ADAPTIVE, BF16, KC, NT, PIPE, true>(hp, w, ms, a, q, n4);
+            batch_quad<ADAPTIVE, MOM, BF16, KC, NT, PIPE, true>(hp, w, ms, a, q, n4);
     }
     if (blockIdx.x == 0) {
         const size_t i = 4 * n4 + threadIdx.x;
@@ -367,14 +380,14 @@ push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, Batch
             float wi = w[i];
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
-            float vi = hp.vel ? hp.vel[i] : 0.f;
+            float vi = load_vel1<MOM>(hp, i);
             for (int k = 0; k < a.K; ++k) {
-                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[k], i), a.bak[k][i], wi, si, vi);
+                apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(a.grad[k], i), a.bak[k][i], wi, si, vi);
                 a.bak[k][i] = wi;
             }
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
-            if (hp.vel) hp.vel[i] = vi;
+            store_vel1<MOM>(hp, i, vi);
         }
     }
 }
@@ -390,7 +403,7 @@ struct FoldArgs {
     int J;
 };
 
-template <bool ADAPTIVE, bool BF16, int KC, bool NT, bool CHECKED>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool CHECKED>
 __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w,
                                           float* __restrict__ ms, const FoldArgs& a,
                                           size_t q, size_t n4) {
@@ -399,25 +412,25 @@ __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w
     f32x4 W = anchor;
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
-    f32x4 V = load_vel4(hp, q);
+    f32x4 V = load_vel4<MOM>(hp, q);
     const int full = (a.J / KC) * KC;
     for (int j0 = 0; j0 < full; j0 += KC) {
         f32x4 G[KC];
 #pragma unroll
         for (int jj = 0; jj < KC; ++jj) G[jj] = load_grad4<BF16, NT>(a.grad[j0 + jj], q);
 #pragma unroll
-        for (int jj = 0; jj < KC; ++jj) apply_push4<ADAPTIVE>(hp, G[jj], anchor, W, S, V);
+        for (int jj = 0; jj < KC; ++jj) apply_push4<ADAPTIVE, MOM>(hp, G[jj], anchor, W, S, V);
     }
     for (int j = full; j < a.J; ++j) {
         const f32x4 g = load_grad4<BF16, NT>(a.grad[j], q);
-        apply_push4<ADAPTIVE>(hp, g, anchor, W, S, V);
+        apply_push4<ADAPTIVE, MOM>(hp, g, anchor, W, S, V);
     }
     store4<false>(w, q, W);
     if constexpr (ADAPTIVE) store4<false>(ms, q, S);
-    store_vel4(hp, q, V);
+    store_vel4<MOM>(hp, q, V);
 }
 
-template <bool ADAPTIVE, bool BF16, int KC, bool NT>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT>
 __global__ void __launch_bounds__(256)
 sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldArgs a,
                  size_t n4, size_t d) {
@@ -425,9 +438,9 @@ sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldAr
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t q = tile * blockDim.x + threadIdx.x;
         if ((tile + 1) * blockDim.x <= n4)
-            fold_quad<ADAPTIVE, BF16, KC, NT, false>(hp, w, ms, a, q, n4);
+            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, false>(hp, w, ms, a, q, n4);
         else
-            fold_quad<ADAPTIVE, BF16, KC, NT, true>(hp, w, ms, a, q, n4);
+            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, true>(hp, w, ms, a, q, n4);
     }
     if (blockIdx.x == 0) {
         const size_t i = 4 * n4 + threadIdx.x;
@@ -436,12 +449,12 @@ sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldAr
             float wi = anchor;
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
-            float vi = hp.vel ? hp.vel[i] : 0.f;
+            float vi = load_vel1<MOM>(hp, i);
             for (int j = 0; j < a.J; ++j)
-                apply_push<ADAPTIVE>(hp, load_grad1<BF16>(a.grad[j], i), anchor, wi, si, vi);
+                apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(a.grad[j], i), anchor, wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
-            if (hp.vel) hp.vel[i] = vi;
+            store_vel1<MOM>(hp, i, vi);
         }
     }
 }
@@ -664,7 +677,7 @@ __device__ __forceinline__ float synth_delivered(float snap, float h, float wsta
     else return g;
 }
 
-template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS, bool CHECKED>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, bool CHECKED>
 __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restrict__ w,
                                                 float* __restrict__ ms, float* __restrict__ bak,
                                                 const float* __restrict__ hdiag,
@@ -676,7 +689,7 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
     for (int j = 0; j < ITEMS; ++j) {
         const size_t q = first + (size_t)j * blockDim.x;
         if (!CHECKED || q < n4) {
-            V[j] = load_vel4(hp, q);
+            V[j] = load_vel4<MOM>(hp, q);
             B[j] = load4<true>(bak, q);
             H[j] = load4<true>(hdiag, q);
             O[j] = load4<true>(wstar, q);
@@ -696,8 +709,8 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 g[c] = synth_delivered<BF16>(B[j][c], H[j][c], O[j][c], sigma, z[c]);
-            apply_push4<ADAPTIVE>(hp, g, B[j], W[j], S[j], V[j]);
-            store_vel4(hp, q, V[j]);
+            apply_push4<ADAPTIVE, MOM>(hp, g, B[j], W[j], S[j], V[j]);
+            store_vel4<MOM>(hp, q, V[j]);
             store4<true>(w, q, W[j]);
             if constexpr (ADAPTIVE) store4<true>(ms, q, S[j]);
             if constexpr (PULL) store4<true>(bak, q, W[j]);
@@ -705,7 +718,7 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
     }
 }
 
-template <bool ADAPTIVE, bool BF16, bool PULL, int ITEMS>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS>
 __global__ void __launch_bounds__(512)
 push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
                   float* __restrict__ bak, const float* __restrict__ hdiag,
@@ -716,10 +729,10 @@ push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t first = tile * tile_quads + threadIdx.x;
         if ((tile + 1) * tile_quads <= n4)
-            push_synth_tile<ADAPTIVE, BF16, PULL, ITEMS, false>(hp, w, ms, bak, hdiag, wstar, sigma,
+            push_synth_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, false>(hp, w, ms, bak, hdiag, wstar, sigma,
                                                                 k0, k1, t, first, n4);
         else
-            push_synth_tile<ADAPTIVE, BF16, PULL, ITEMS, true>(hp, w, ms, bak, hdiag, wstar, sigma,
+            push_synth_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, true>(hp, w, ms, bak, hdiag, wstar, sigma,
                                                                k0, k1, t, first, n4);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0 && 4 * n4 < d) {
@@ -730,12 +743,12 @@ push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
             float wi = w[i];
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
-            float vi = hp.vel ? hp.vel[i] : 0.f;
-            apply_push<ADAPTIVE>(hp, g, b, wi, si, vi);
+            float vi = load_vel1<MOM>(hp, i);
+            apply_push<ADAPTIVE, MOM>(hp, g, b, wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
             if constexpr (PULL) bak[i] = wi;
-            if (hp.vel) hp.vel[i] = vi;
+            store_vel1<MOM>(hp, i, vi);
         }
     }
 }
