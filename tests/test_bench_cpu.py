@@ -1,0 +1,32 @@
+"""Host-side pieces of bench.py that need no GPU."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+
+def test_algorithmic_bytes_per_update():
+    import bench
+    from paper_1609_08326_amd import workloads as W
+    c = W.CONFIGS
+    assert bench.algorithmic_bytes_per_update(c[0]) == 20      # c: w, bak, g in; w, bak out
+    assert bench.algorithmic_bytes_per_update(c[1]) == 28      # a: + MeanSquare in and out
+    assert bench.algorithmic_bytes_per_update(c[2]) == 28
+    assert bench.algorithmic_bytes_per_update(c[3]) == 13      # (16 + 16*12) / 16
+    assert bench.algorithmic_bytes_per_update(c[4]) == 26      # bf16 gradient
+    assert bench.algorithmic_bytes_per_update(W.get("fold")) == 5
+
+
+def test_more_than_one_gpu_is_refused():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_profile_figures_are_read_from_the_committed_summaries():
+    import bench
+    assert bench.read_profile("push_fused_cfg2") > 7.0e8
+    assert bench.read_profile("sync_fold_J16_fold", "valu_instr_per_launch") > 1e8
+    assert bench.read_profile("no_such_kernel") is None
