@@ -273,3 +273,43 @@ def test_non_default_stream_and_pull_stream_rule():
     assert_same_bits(sv.w.cpu().numpy(), ref.w(), "side-stream w")
     for m in range(wl.M):
         assert_same_bits(sv.bak[m, : wl.d].cpu().numpy(), ref.bak(m), "side-stream bak[%d]" % m)
+
+
+def test_pushes_replay_correctly_from_a_captured_graph():
+    """The library's launches can be captured in a HIP graph (no memset nodes, no
+    allocation, nothing host-dependent in the kernels).  Replays are checked one
+    by one against the oracle, with eager work and synchronisation in between.
+    The handle's host-side counter t does not advance on replays."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    rng = np.random.default_rng(77)
+    d, M = 60013, 3
+    w0 = rng.standard_normal(d).astype(np.float32)
+    g_host = [(0.1 * rng.standard_normal(d)).astype(np.float32) for _ in range(2)]
+    g_dev = [torch.from_numpy(x).cuda() for x in g_host]
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        sv = B.Server(torch.from_numpy(w0).cuda(), M, 0.05, 2.0, B.MODE_A, 0.95, 1e-7,
+                      pull_on_push=True)
+        sv.push(2, g_dev[0])                       # eager warm-up on the capture stream
+    side.synchronize()
+    ref = oracle.Server(w0, M, 0.05, 2.0, oracle.MODE_A, 0.95, 1e-7)
+    ref.push(2, g_host[0]); ref.pull(2)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sv.push(0, g_dev[0])
+        sv.push(1, g_dev[1])
+    t_after_capture = sv.t
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for replay in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        ref.push(0, g_host[0]); ref.pull(0)
+        ref.push(1, g_host[1]); ref.pull(1)
+        assert_same_bits(sv.w.cpu().numpy(), ref.w(), "graph replay %d w" % replay)
+        assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "graph replay %d ms" % replay)
+        assert_same_bits(sv.bak[1, :d].cpu().numpy(), ref.bak(1), "graph replay %d bak" % replay)
+        scratch.add_(1.0)                          # unrelated eager work between replays
+        torch.cuda.synchronize()
+    assert sv.t == t_after_capture
