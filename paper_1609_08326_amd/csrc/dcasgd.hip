@@ -96,7 +96,8 @@ int check_grad(dcasgd_t h, const void* grad) {
     const size_t gb = grad_bytes(h);
     if (overlaps(grad, gb, h->w, h->d * 4) ||
         overlaps(grad, gb, h->bak, (size_t)h->M * h->bak_stride * 4) ||
-        (h->ms && overlaps(grad, gb, h->ms, h->d * 4)))
+        (h->ms && overlaps(grad, gb, h->ms, h->d * 4)) ||
+        (h->hp.vel && overlaps(grad, gb, h->hp.vel, h->d * 4)))
         return DCASGD_EINVAL;
     return DCASGD_OK;
 }
@@ -123,9 +124,9 @@ void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipSt
         with_bool(fuse_pull, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
             with_level(h->streaming, [&](auto NT) {
-                hipLaunchKernelGGL((push_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value,
-                                                decltype(PL)::value, decltype(IT)::value,
-                                                decltype(NT)::value>),
+                hipLaunchKernelGGL((push_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                decltype(BF)::value, decltype(PL)::value,
+                                                decltype(IT)::value, decltype(NT)::value>),
                                    dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row,
                                    grad, n4, h->d);
             });
@@ -152,9 +153,9 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value,
-                                                  DCASGD_BATCH_KC, decltype(NT)::value,
-                                                  (DCASGD_BATCH_PIPE != 0)>),
+            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                  decltype(BF)::value, DCASGD_BATCH_KC,
+                                                  decltype(NT)::value, (DCASGD_BATCH_PIPE != 0)>),
                                dim3(grid), dim3(threads), 0, s, h->hp, h->w, h->ms, a, n4, h->d);
         });
       });
@@ -215,6 +216,8 @@ int dcasgd_bind(dcasgd_t h, float* w, float* bak, size_t bak_stride, float* ms) 
     h->bak = bak;
     h->bak_stride = bak_stride;
     h->ms = ms;
+    h->hp.mu = 0.0f;          // a velocity vector belongs to the state it was set up for
+    h->hp.vel = nullptr;
     h->bound = true;
     h->ready = false;
     return DCASGD_OK;
@@ -292,7 +295,8 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
     const void* loss[2] = {hdiag, wstar};
     for (const void* p : loss)
         if (overlaps(p, vb, h->w, vb) || overlaps(p, vb, h->bak, bb) ||
-            (h->ms && overlaps(p, vb, h->ms, vb)))
+            (h->ms && overlaps(p, vb, h->ms, vb)) ||
+            (h->hp.vel && overlaps(p, vb, h->hp.vel, vb)))
             return fail(h, DCASGD_EINVAL);
     const size_t n4 = h->d / 4;
     float* row = h->bak + (size_t)worker * h->bak_stride;
@@ -305,8 +309,9 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->pull_on_push, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
-              hipLaunchKernelGGL((push_synth_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value,
-                                                    decltype(PL)::value, decltype(IT)::value>),
+              hipLaunchKernelGGL((push_synth_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                    decltype(BF)::value, decltype(PL)::value,
+                                                    decltype(IT)::value>),
                                  dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row, hdiag,
                                  wstar, sigma, k0, k1, push_idx, n4, h->d);
           });
@@ -341,8 +346,8 @@ int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat,
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((sync_fold_kernel<decltype(AD)::value, decltype(MO)::value, decltype(BF)::value, 4,
-                                                 decltype(NT)::value>),
+            hipLaunchKernelGGL((sync_fold_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                 decltype(BF)::value, 4, decltype(NT)::value>),
                                dim3(grid), dim3(threads), 0, s, hp, h->w, h->ms, a, n4, h->d);
         });
       });

@@ -3,10 +3,11 @@
 // Everything here is elementwise streaming work: each parameter is read,
 // updated and written once per push, with no reuse inside a launch.  The
 // kernels are therefore built around 128-bit global loads and stores issued
-// up front (ITEMS independent float4 groups per lane), non-temporal hints for
-// the traffic that is not touched again soon (gradients, backups), and enough
-// resident wavefronts to keep HBM busy.  There is no LDS use and no MFMA: no
-// operand is shared between lanes.
+// up front (ITEMS independent float4 groups per lane), non-temporal hints
+// (gradients and backups are not touched again for a whole cycle of pushes;
+// measured on MI355X, streaming loads and stores are also the faster choice
+// for w and MeanSquare), and enough resident wavefronts to keep HBM busy.
+// There is no LDS use and no MFMA: no operand is shared between lanes.
 //
 // Arithmetic contract (matches the header of the C ABI): binary32, one rounding
 // per operation, no contraction, correctly rounded sqrt and division.
