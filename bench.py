@@ -106,7 +106,10 @@ def main() -> int:
                     help="also time the worker+push fusion (dcasgd_push_synth) and report it "
                          "under 'fused_worker_path'; K=1 workloads only")
     ap.add_argument("--no-events", action="store_true",
-                    help="skip per-kernel events (whole-path timing only)")
+                    help="no per-kernel events at all (whole-path timing only)")
+    ap.add_argument("--stream-events", action="store_true",
+                    help="additionally record stream events between the kernels of a step and "
+                         "report their intervals (adds a dispatch gap per event)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU oracle sample length; 0 skips the baseline")
     args = ap.parse_args()
@@ -139,9 +142,15 @@ def main() -> int:
     gdt = torch.bfloat16 if wl.grad_bf16 else torch.float32
     gbuf = [torch.empty(wl.d, dtype=gdt, device=dev) for _ in range(K)]
 
+    # Server-update launches carry their own start/stop HIP events (attached to
+    # the kernel by the library), so their distance is the kernel's duration.
     use_events = not args.no_events
+    # (launch-bound 1 MB workloads: the extra host work of an event-carrying
+    # launch would dominate, so they are timed by stream events instead)
+    kernel_events = use_events and wl.d * 4 >= (16 << 20)
+    stream_events = use_events and (args.stream_events or not kernel_events)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_steps)] \
-        if use_events else None
+        if stream_events else None
 
     def step(i: int, rec) -> None:
         base = i * K
@@ -165,11 +174,15 @@ def main() -> int:
     for i in range(n_warm):
         step(i, None)
     torch.cuda.synchronize()
+    if kernel_events:
+        sv.timing(True)
     t0 = time.perf_counter()
     for i in range(n_steps):
-        step(n_warm + i, ev[i] if use_events else None)
+        step(n_warm + i, ev[i] if stream_events else None)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    kernel_ms, kernel_launches = sv.timing_read() if kernel_events else (0.0, 0)
+    sv.timing(False)
 
     updates = wl.d * K * n_steps
     value = updates / elapsed
@@ -194,8 +207,11 @@ def main() -> int:
                             "synth_grad x%d + fused push+pull") % K},
     }
     if use_events:
-        synth_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / n_steps
-        push_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / n_steps
+        if kernel_events:
+            push_ms = kernel_ms / n_steps        # server-update kernel time per step
+        else:
+            push_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / n_steps
+            kernel_launches = n_steps
         launch_bytes = bpu * wl.d * K
         achieved = launch_bytes / (push_ms * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": achieved,
@@ -218,9 +234,17 @@ def main() -> int:
                                "bytes_per_element_update": bpu}
         out["server_update_only"] = {"value": wl.d * K / (push_ms * 1e-3),
                                      "unit": "element-updates/s"}
-        synth_bytes = (12 + (2 if wl.grad_bf16 else 4)) * wl.d * K
-        out["worker_kernel"] = {"kernel": "synth_grad", "avg_ms_per_step": synth_ms,
-                                "achieved_GBs": synth_bytes / (synth_ms * 1e-3) / 1e9}
+        out["roofline"]["launches_timed"] = kernel_launches
+        out["roofline"]["timed_by"] = ("HIP events attached to each launch" if kernel_events
+                                       else "HIP stream events around each launch")
+        out["worker_and_gaps_ms_per_step"] = 1e3 * elapsed / n_steps - push_ms
+        if stream_events:
+            synth_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / n_steps
+            synth_bytes = (12 + (2 if wl.grad_bf16 else 4)) * wl.d * K
+            out["stream_event_intervals"] = {
+                "worker_ms_per_step": synth_ms,
+                "server_ms_per_step": sum(e[1].elapsed_time(e[2]) for e in ev) / n_steps,
+                "worker_achieved_GBs": synth_bytes / (synth_ms * 1e-3) / 1e9}
     if args.fused_worker and K == 1:
         # same arrivals, one launch per arrival: the gradient never leaves registers
         torch.cuda.synchronize()

@@ -152,6 +152,21 @@ const char* dcasgd_strerror(int code);
 int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream);
 
 /*
+ * Per-launch timing of the server-update kernels (push, push_batch,
+ * push_synth, sync_fold).  While enabled, every such launch carries its own
+ * start and stop HIP events, attached to the kernel itself, so their distance
+ * is the kernel's execution time with no dispatch gap in it.  Events are host
+ * objects created on demand and reused.  Do not enable it around launches
+ * that are being captured into a HIP graph.
+ * dcasgd_timing(h, enable) switches it and forgets unread launches;
+ * dcasgd_timing_read waits for the last timed launch, returns the summed
+ * kernel time in milliseconds and the number of launches since the last read
+ * (host pointers), and starts a new interval.
+ */
+int dcasgd_timing(dcasgd_t h, int enable);
+int dcasgd_timing_read(dcasgd_t h, double* total_ms, uint64_t* launches);
+
+/*
  * Change the learning rate for all later pushes (the experiments of Section 6
  * divide it by ten at fixed epochs).  Pushes already enqueued keep the value
  * they were launched with.  eta must be finite.

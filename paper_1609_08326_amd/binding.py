@@ -41,6 +41,8 @@ _PROTOTYPES = {
     "dcasgd_last_error": (C.c_int, [C.c_void_p]),
     "dcasgd_strerror": (C.c_char_p, [C.c_int]),
     "dcasgd_set_momentum": (C.c_int, [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]),
+    "dcasgd_timing": (C.c_int, [C.c_void_p, C.c_int]),
+    "dcasgd_timing_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
     "dcasgd_set_eta": (C.c_int, [C.c_void_p, C.c_float]),
     "dcasgd_set_launch": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]),
     "dcasgd_synth_grad": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_uint64,
@@ -164,6 +166,16 @@ class Server:
         self.vel = torch.empty(self.d, dtype=torch.float32, device=self.w.device)
         _check(load().dcasgd_set_momentum(self._h, float(mu), self.vel.data_ptr(),
                                           _stream_ptr(stream)), "dcasgd_set_momentum")
+
+    def timing(self, enable: bool) -> None:
+        """Attach start/stop HIP events to every server-update launch from now on."""
+        _check(load().dcasgd_timing(self._h, int(bool(enable))), "dcasgd_timing")
+
+    def timing_read(self):
+        """(summed kernel milliseconds, launches) since the last read; waits for them."""
+        ms, n = C.c_double(0.0), C.c_uint64(0)
+        _check(load().dcasgd_timing_read(self._h, C.byref(ms), C.byref(n)), "dcasgd_timing_read")
+        return float(ms.value), int(n.value)
 
     def set_eta(self, eta: float) -> None:
         """Learning rate of all later pushes (step schedules)."""

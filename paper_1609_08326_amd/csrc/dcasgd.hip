@@ -8,6 +8,8 @@
 #include <type_traits>
 #include <vector>
 
+#include <hip/hip_ext.h>
+
 #include "dcasgd_kernels.hip.h"
 
 using namespace dcasgd;
@@ -38,6 +40,10 @@ struct dcasgd_server {
     int batch_threads = 64;           // the queue kernel does 16x the work per lane: one wave per block
     int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything
     int last_error = DCASGD_OK;
+    // optional per-launch timing of the server-update kernels
+    bool timing = false;
+    std::vector<hipEvent_t> timing_events;   // start, stop, start, stop, ...
+    size_t timing_used = 0;                  // events handed out since the last read
 };
 
 namespace {
@@ -84,6 +90,32 @@ inline unsigned grid_for(size_t n4, size_t per_block, int max_blocks) {
     return (unsigned)tiles;
 }
 
+// Two events of their own for the next timed launch (created on demand, reused).
+inline bool next_event_pair(dcasgd_t h, hipEvent_t* start, hipEvent_t* stop) {
+    while (h->timing_events.size() < h->timing_used + 2) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return false;
+        h->timing_events.push_back(e);
+    }
+    *start = h->timing_events[h->timing_used];
+    *stop = h->timing_events[h->timing_used + 1];
+    h->timing_used += 2;
+    return true;
+}
+
+// Launch of a server-update kernel.  With timing on, the launch itself carries
+// a start and a stop event (hipExtLaunchKernelGGL), so the pair brackets the
+// kernel's execution and nothing else; no extra packet goes into the stream.
+#define DCASGD_LAUNCH(h, kern, grid, block, s, ...)                                          \
+    do {                                                                                       \
+        hipEvent_t ev0_ = nullptr, ev1_ = nullptr;                                             \
+        if ((h)->timing && next_event_pair((h), &ev0_, &ev1_))                                 \
+            hipExtLaunchKernelGGL(kern, dim3(grid), dim3(block), 0, s, ev0_, ev1_, 0,          \
+                                  __VA_ARGS__);                                                \
+        else                                                                                   \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(block), 0, s, __VA_ARGS__);              \
+    } while (0)
+
 inline int launched(dcasgd_t h) {
     return hipGetLastError() == hipSuccess ? DCASGD_OK : fail(h, DCASGD_EHIP);
 }
@@ -124,11 +156,10 @@ void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipSt
         with_bool(fuse_pull, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
             with_level(h->streaming, [&](auto NT) {
-                hipLaunchKernelGGL((push_kernel<decltype(AD)::value, decltype(MO)::value,
-                                                decltype(BF)::value, decltype(PL)::value,
-                                                decltype(IT)::value, decltype(NT)::value>),
-                                   dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row,
-                                   grad, n4, h->d);
+                DCASGD_LAUNCH(h, (push_kernel<decltype(AD)::value, decltype(MO)::value,
+                                              decltype(BF)::value, decltype(PL)::value,
+                                              decltype(IT)::value, decltype(NT)::value>),
+                              grid, h->threads, s, h->hp, h->w, h->ms, row, grad, n4, h->d);
             });
           });
         });
@@ -153,10 +184,10 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((push_batch_kernel<decltype(AD)::value, decltype(MO)::value,
-                                                  decltype(BF)::value, DCASGD_BATCH_KC,
-                                                  decltype(NT)::value, (DCASGD_BATCH_PIPE != 0)>),
-                               dim3(grid), dim3(threads), 0, s, h->hp, h->w, h->ms, a, n4, h->d);
+            DCASGD_LAUNCH(h, (push_batch_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                decltype(BF)::value, DCASGD_BATCH_KC,
+                                                decltype(NT)::value, (DCASGD_BATCH_PIPE != 0)>),
+                          grid, threads, s, h->hp, h->w, h->ms, a, n4, h->d);
         });
       });
      });
@@ -199,6 +230,7 @@ dcasgd_t dcasgd_create(size_t d, int M, float eta, float lambda0, int mode, floa
 
 int dcasgd_destroy(dcasgd_t h) {
     if (!h) return DCASGD_EINVAL;
+    for (hipEvent_t e : h->timing_events) (void)hipEventDestroy(e);
     delete h;
     return DCASGD_OK;
 }
@@ -309,11 +341,11 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->pull_on_push, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
-              hipLaunchKernelGGL((push_synth_kernel<decltype(AD)::value, decltype(MO)::value,
-                                                    decltype(BF)::value, decltype(PL)::value,
-                                                    decltype(IT)::value>),
-                                 dim3(grid), dim3(h->threads), 0, s, h->hp, h->w, h->ms, row, hdiag,
-                                 wstar, sigma, k0, k1, push_idx, n4, h->d);
+              DCASGD_LAUNCH(h, (push_synth_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                  decltype(BF)::value, decltype(PL)::value,
+                                                  decltype(IT)::value>),
+                            grid, h->threads, s, h->hp, h->w, h->ms, row, hdiag, wstar, sigma, k0,
+                            k1, push_idx, n4, h->d);
           });
         });
       });
@@ -346,9 +378,9 @@ int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat,
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((sync_fold_kernel<decltype(AD)::value, decltype(MO)::value,
-                                                 decltype(BF)::value, 4, decltype(NT)::value>),
-                               dim3(grid), dim3(threads), 0, s, hp, h->w, h->ms, a, n4, h->d);
+            DCASGD_LAUNCH(h, (sync_fold_kernel<decltype(AD)::value, decltype(MO)::value,
+                                               decltype(BF)::value, 4, decltype(NT)::value>),
+                          grid, threads, s, hp, h->w, h->ms, a, n4, h->d);
         });
       });
      });
@@ -408,6 +440,33 @@ int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream) {
     h->hp.vel = vel;
     h->stream = s;
     return launched(h);
+}
+
+int dcasgd_timing(dcasgd_t h, int enable) {
+    if (!h) return DCASGD_EINVAL;
+    h->timing = enable != 0;
+    h->timing_used = 0;
+    return DCASGD_OK;
+}
+
+int dcasgd_timing_read(dcasgd_t h, double* total_ms, uint64_t* launches) {
+    if (!h) return DCASGD_EINVAL;
+    if (!total_ms || !launches) return fail(h, DCASGD_EINVAL);
+    double sum = 0.0;
+    const size_t n = h->timing_used;
+    if (n >= 2 && hipEventSynchronize(h->timing_events[n - 1]) != hipSuccess)
+        return fail(h, DCASGD_EHIP);
+    for (size_t i = 0; i + 1 < n; i += 2) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(h->timing_events[i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, h->timing_events[i], h->timing_events[i + 1]) != hipSuccess)
+            return fail(h, DCASGD_EHIP);
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = n / 2;
+    h->timing_used = 0;
+    return DCASGD_OK;
 }
 
 int dcasgd_set_eta(dcasgd_t h, float eta) {

@@ -313,3 +313,33 @@ def test_pushes_replay_correctly_from_a_captured_graph():
         scratch.add_(1.0)                          # unrelated eager work between replays
         torch.cuda.synchronize()
     assert sv.t == t_after_capture
+
+
+def test_per_launch_timing_counts_launches_and_changes_nothing():
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = small(300007, M=3, T=10)
+    timed = GpuRun(wl)          # baseline run, untimed
+    hd, ws = torch.from_numpy(timed.hdiag_host).cuda(), torch.from_numpy(timed.wstar_host).cuda()
+    sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
+                  wl.eps, pull_on_push=True)
+    g = torch.empty(wl.d, device="cuda")
+    sv.timing(True)
+    for t, m in enumerate(timed.arrivals):
+        B.synth_grad(sv.snapshot(int(m)), hd, ws, wl.sigma, wl.seed, t, g)
+        sv.push(int(m), g)
+    ms, n = sv.timing_read()
+    assert n == len(timed.arrivals) and 0.0 < ms < 1000.0
+    assert sv.timing_read() == (0.0, 0)          # a read starts a new interval
+    sv.timing(False)
+    sv.push(0, g)
+    assert sv.timing_read() == (0.0, 0)
+    torch.cuda.synchronize()
+    sv2 = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
+                   wl.eps, pull_on_push=True)
+    sv2.timing(True)
+    for t, m in enumerate(timed.arrivals):
+        B.synth_grad(sv2.snapshot(int(m)), hd, ws, wl.sigma, wl.seed, t, g)
+        sv2.push(int(m), g)
+    torch.cuda.synchronize()
+    assert_same_bits(sv2.w.cpu().numpy(), timed.w, "timed launches give the same w")
