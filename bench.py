@@ -115,7 +115,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by index range, "
-              "see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+              "one GPU holds one shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         return 2
 
     import torch

@@ -23,7 +23,7 @@ def assert_same_bits(got: np.ndarray, ref: np.ndarray, what: str) -> None:
                                 float(ref[i]), int(rb[i])))
 
 
-class GpuRun:
+class DeviceRun:
     """State after running a workload through the HIP library."""
 
     def __init__(self, wl: W.Workload, *, fused: bool = True, batched: bool = False,
@@ -99,7 +99,7 @@ def oracle_run(wl: W.Workload, hdiag, wstar, arrivals, idx=None, nthreads: int =
     return sv
 
 
-def compare(run: GpuRun, ref: "oracle.Server", idx=None, tag: str = "") -> None:
+def compare(run: DeviceRun, ref: "oracle.Server", idx=None, tag: str = "") -> None:
     sel = (lambda a: a) if idx is None else (lambda a: a[idx.astype(np.int64)])
     w_ref = ref.w()
     assert np.all(np.isfinite(w_ref)), tag + " oracle produced non-finite w"

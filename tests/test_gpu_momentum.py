@@ -9,7 +9,7 @@ import pytest
 import oracle
 from paper_1609_08326_amd import workloads as W
 
-from gpu_harness import GpuRun, assert_same_bits, compare, oracle_run
+from gpu_harness import DeviceRun, assert_same_bits, compare, oracle_run
 
 pytestmark = pytest.mark.gpu
 
@@ -33,7 +33,7 @@ def test_push_with_momentum(mode, bf16):
         for fused in (True, False):
             wl = small(d, mode=mode, bf16=bf16)
             say("momentum push d=%d mode=%d bf16=%s fused=%s" % (d, mode, bf16, fused))
-            run = GpuRun(wl, fused=fused, momentum=0.9)
+            run = DeviceRun(wl, fused=fused, momentum=0.9)
             ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1, momentum=0.9)
             compare(run, ref, tag="momentum d=%d" % d)
 
@@ -44,7 +44,7 @@ def test_push_batch_with_momentum(mode):
         for K in (3, 16):
             wl = small(d, M=16, T=2 * K, mode=mode, order="queues", K=K)
             say("momentum batch d=%d K=%d mode=%d" % (d, K, mode))
-            run = GpuRun(wl, batched=True, momentum=0.5)
+            run = DeviceRun(wl, batched=True, momentum=0.5)
             ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1, momentum=0.5)
             compare(run, ref, tag="momentum batch")
 
@@ -85,7 +85,7 @@ def test_push_synth_and_fold_with_momentum_and_switching_off():
 def test_momentum_full_size_sampled():
     wl = W.CONFIGS[2].replace(T=60)
     say("momentum full size %s" % wl.name)
-    run = GpuRun(wl, momentum=0.9)
+    run = DeviceRun(wl, momentum=0.9)
     idx = wl.sample_indices(100_000, edge=4096)
     ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, idx=idx, nthreads=16, momentum=0.9)
     compare(run, ref, idx=idx, tag="momentum cfg2")

@@ -11,7 +11,7 @@ import pytest
 import oracle
 from paper_1609_08326_amd import workloads as W
 
-from gpu_harness import GpuRun, assert_same_bits, compare, oracle_run
+from gpu_harness import DeviceRun, assert_same_bits, compare, oracle_run
 
 pytestmark = pytest.mark.gpu
 
@@ -60,7 +60,7 @@ def test_small_sizes_every_tail(mode, bf16, fused):
                        dict(threads=256, items=1, streaming=2)):
             wl = small(d, mode=mode, bf16=bf16)
             say("small d=%d mode=%d bf16=%s fused=%s launch=%s" % (d, mode, bf16, fused, launch))
-            run = GpuRun(wl, fused=fused, launch=launch)
+            run = DeviceRun(wl, fused=fused, launch=launch)
             ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1)
             compare(run, ref, tag="d=%d" % d)
 
@@ -72,10 +72,10 @@ def test_push_batch_equals_unbatched_and_oracle(mode, bf16):
         for K in (1, 2, 5, 8, 16):
             wl = small(d, M=16, T=3 * K, mode=mode, bf16=bf16, order="queues", K=K)
             say("batch d=%d K=%d mode=%d bf16=%s" % (d, K, mode, bf16))
-            run = GpuRun(wl, batched=True, launch=dict(threads=128, items=1))
+            run = DeviceRun(wl, batched=True, launch=dict(threads=128, items=1))
             ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1)
             compare(run, ref, tag="batched d=%d K=%d" % (d, K))
-            plain = GpuRun(wl, batched=False)
+            plain = DeviceRun(wl, batched=False)
             assert_same_bits(run.w, plain.w, "batched vs unbatched w")
 
 
@@ -83,7 +83,7 @@ def test_push_batch_with_repeated_workers():
     """A queue that names a worker twice is split at the repeat."""
     wl = small(5003, M=4, T=32, order="iid", K=8, seed=5)
     say("batch with repeats")
-    run = GpuRun(wl, batched=True)
+    run = DeviceRun(wl, batched=True)
     assert any(len(set(run.arrivals[i:i + 8])) < 8 for i in range(0, 32, 8))
     ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1)
     compare(run, ref, tag="repeats")
@@ -94,7 +94,7 @@ def test_config_full_elementwise(cfg):
     """Configurations 0 and 1 (ResNet-20-sized): every element, every push."""
     wl = W.CONFIGS[cfg]
     say("full config %s" % wl.name)
-    run = GpuRun(wl)
+    run = DeviceRun(wl)
     ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=16)
     compare(run, ref, tag=wl.name)
 
@@ -107,7 +107,7 @@ def test_config_full_size_sampled(cfg):
     element's history is complete."""
     wl = W.CONFIGS[cfg]
     say("full-size sampled config %s" % wl.name)
-    run = GpuRun(wl, batched=(wl.K > 1))
+    run = DeviceRun(wl, batched=(wl.K > 1))
     idx = wl.sample_indices(150_000, edge=4096)
     ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, idx=idx, nthreads=16)
     compare(run, ref, idx=idx, tag=wl.name)
@@ -245,7 +245,7 @@ def test_degenerate_settings_on_the_gpu():
                small(5001, M=1, mode=W.MODE_A),
                small(5001, M=3, mode=W.MODE_A).replace(ema_m=0.0)):
         say("degenerate %s" % (wl,))
-        run = GpuRun(wl)
+        run = DeviceRun(wl)
         ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=1)
         compare(run, ref, tag="degenerate")
 
@@ -319,7 +319,7 @@ def test_per_launch_timing_counts_launches_and_changes_nothing():
     import torch
     from paper_1609_08326_amd import binding as B
     wl = small(300007, M=3, T=10)
-    timed = GpuRun(wl)          # baseline run, untimed
+    timed = DeviceRun(wl)          # baseline run, untimed
     hd, ws = torch.from_numpy(timed.hdiag_host).cuda(), torch.from_numpy(timed.wstar_host).cuda()
     sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
                   wl.eps, pull_on_push=True)

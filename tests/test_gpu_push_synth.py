@@ -8,7 +8,7 @@ import pytest
 
 from paper_1609_08326_amd import workloads as W
 
-from gpu_harness import GpuRun, assert_same_bits, oracle_run
+from gpu_harness import DeviceRun, assert_same_bits, oracle_run
 
 pytestmark = pytest.mark.gpu
 
@@ -77,7 +77,7 @@ def test_push_synth_full_size_sampled(cfg):
 def test_push_synth_equals_separate_launches():
     wl = W.CONFIGS[1].replace(T=60)
     sv, _, _, _ = run_fused(wl)
-    plain = GpuRun(wl)
+    plain = DeviceRun(wl)
     assert_same_bits(sv.w.cpu().numpy(), plain.w, "fused vs separate w")
     assert_same_bits(sv.ms.cpu().numpy(), plain.ms, "fused vs separate ms")
     assert_same_bits(sv.bak[:, : wl.d].cpu().numpy().ravel(), plain.bak.ravel(), "fused vs separate bak")

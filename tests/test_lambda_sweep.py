@@ -59,7 +59,7 @@ def test_oracle_lambda_regimes():
 
 @pytest.mark.gpu
 def test_gpu_reproduces_the_oracle_table():
-    from gpu_harness import GpuRun, assert_same_bits
+    from gpu_harness import DeviceRun, assert_same_bits
     h, ws, order = _problem()
     for mode, eta, lam in ((W.MODE_C, 0.2, 0.0), (W.MODE_C, 0.2, 1.0), (W.MODE_A, 0.2, 0.5),
                            (W.MODE_C, 0.4, 0.2), (W.MODE_C, 0.4, 0.0), (W.MODE_A, 0.2, 8.0)):
@@ -67,7 +67,7 @@ def test_gpu_reproduces_the_oracle_table():
                         eps=1e-7, h_lo=1e-2, h_hi=1.0, wstar_sigma=1.0, sigma=0.05,
                         order="round_robin", seed=SEED)
         print("sweep mode=%d eta=%g lambda=%g" % (mode, eta, lam), flush=True)
-        run = GpuRun(wl, hdiag=h, wstar=ws, arrivals=order)
+        run = DeviceRun(wl, hdiag=h, wstar=ws, arrivals=order)
         ref_loss, ref_w = _oracle_loss(mode, eta, lam, 0.05)
         if math.isfinite(ref_loss) and np.all(np.isfinite(ref_w)):
             assert_same_bits(run.w, ref_w, "sweep w")
