@@ -152,6 +152,33 @@ const char* dcasgd_strerror(int code);
 int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream);
 
 /*
+ * Launch-bound use (small models): keep a copy of the push counter t in
+ * device memory so that sequences of launches can be captured into a HIP
+ * graph and replayed.  counter: device pointer to one uint32, 4-byte aligned,
+ * owned by the caller, not overlapping the state; it is set to t on stream.
+ * From then on every push-type call also enqueues a one-lane kernel that
+ * advances it (by 1, K or J), and worker gradients formed through the handle
+ * (dcasgd_worker_grad, dcasgd_push_synth) read the push index that keys their
+ * noise from it when they run instead of taking it as a launch argument -
+ * a replayed graph therefore keeps drawing fresh noise.  NULL unbinds.
+ * Replays advance the device counter but not the host's t: call
+ * dcasgd_set_step afterwards with the number of pushes really applied (it
+ * also forgets which backups are current, so the next dcasgd_pull copies).
+ */
+int dcasgd_bind_counter(dcasgd_t h, uint32_t* counter, void* stream);
+int dcasgd_set_step(dcasgd_t h, uint64_t t);
+
+/*
+ * Synthetic worker through the handle: the gradient of worker's current
+ * backup, as dcasgd_synth_grad would form it with push_idx = t + offset
+ * (t read from the device counter if one is bound), written to grad_out in
+ * the handle's gradient type.  offset lets a queue of K gradients be formed
+ * before the K pushes are applied.
+ */
+int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* wstar,
+                       float sigma, uint64_t seed, uint32_t offset, void* grad_out, void* stream);
+
+/*
  * Per-launch timing of the server-update kernels (push, push_batch,
  * push_synth, sync_fold).  While enabled, every such launch carries its own
  * start and stop HIP events, attached to the kernel itself, so their distance

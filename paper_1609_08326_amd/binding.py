@@ -41,6 +41,10 @@ _PROTOTYPES = {
     "dcasgd_last_error": (C.c_int, [C.c_void_p]),
     "dcasgd_strerror": (C.c_char_p, [C.c_int]),
     "dcasgd_set_momentum": (C.c_int, [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]),
+    "dcasgd_bind_counter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dcasgd_set_step": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "dcasgd_worker_grad": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
+                                     C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "dcasgd_timing": (C.c_int, [C.c_void_p, C.c_int]),
     "dcasgd_timing_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
     "dcasgd_set_eta": (C.c_int, [C.c_void_p, C.c_float]),
@@ -166,6 +170,26 @@ class Server:
         self.vel = torch.empty(self.d, dtype=torch.float32, device=self.w.device)
         _check(load().dcasgd_set_momentum(self._h, float(mu), self.vel.data_ptr(),
                                           _stream_ptr(stream)), "dcasgd_set_momentum")
+
+    def bind_counter(self, stream=None) -> None:
+        """Keep the push counter in device memory too (``self.counter``, one int32 owned by
+        torch) so that launch sequences can be captured into a HIP graph and replayed."""
+        import torch
+        self.counter = torch.zeros(1, dtype=torch.int32, device=self.w.device)
+        _check(load().dcasgd_bind_counter(self._h, self.counter.data_ptr(), _stream_ptr(stream)),
+               "dcasgd_bind_counter")
+
+    def set_step(self, t: int) -> None:
+        """Tell the handle how many pushes have been applied (after graph replays)."""
+        _check(load().dcasgd_set_step(self._h, int(t)), "dcasgd_set_step")
+
+    def worker_grad(self, worker: int, hdiag, wstar, sigma: float, seed: int, out,
+                    offset: int = 0, stream=None) -> None:
+        """Synthetic gradient of worker's current backup, noise keyed by t + offset."""
+        assert out.is_cuda and out.dtype == self.grad_dtype and out.numel() == self.d
+        _check(load().dcasgd_worker_grad(self._h, int(worker), hdiag.data_ptr(), wstar.data_ptr(),
+                                         float(sigma), int(seed), int(offset), out.data_ptr(),
+                                         _stream_ptr(stream)), "dcasgd_worker_grad")
 
     def timing(self, enable: bool) -> None:
         """Attach start/stop HIP events to every server-update launch from now on."""

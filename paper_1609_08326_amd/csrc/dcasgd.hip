@@ -40,6 +40,7 @@ struct dcasgd_server {
     int batch_threads = 64;           // the queue kernel does 16x the work per lane: one wave per block
     int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything
     int last_error = DCASGD_OK;
+    uint32_t* ctr = nullptr;          // optional device-resident copy of t (low 32 bits)
     // optional per-launch timing of the server-update kernels
     bool timing = false;
     std::vector<hipEvent_t> timing_events;   // start, stop, start, stop, ...
@@ -115,6 +116,11 @@ inline bool next_event_pair(dcasgd_t h, hipEvent_t* start, hipEvent_t* stop) {
         else                                                                                   \
             hipLaunchKernelGGL(kern, dim3(grid), dim3(block), 0, s, __VA_ARGS__);              \
     } while (0)
+
+// keep the device-resident push counter in step with t after n applied pushes
+inline void advance_counter(dcasgd_t h, uint32_t n, hipStream_t s) {
+    if (h->ctr) hipLaunchKernelGGL(counter_add_kernel, dim3(1), dim3(64), 0, s, h->ctr, n);
+}
 
 inline int launched(dcasgd_t h) {
     return hipGetLastError() == hipSuccess ? DCASGD_OK : fail(h, DCASGD_EHIP);
@@ -250,6 +256,7 @@ int dcasgd_bind(dcasgd_t h, float* w, float* bak, size_t bak_stride, float* ms) 
     h->ms = ms;
     h->hp.mu = 0.0f;          // a velocity vector belongs to the state it was set up for
     h->hp.vel = nullptr;
+    h->ctr = nullptr;
     h->bound = true;
     h->ready = false;
     return DCASGD_OK;
@@ -265,6 +272,7 @@ int dcasgd_init(dcasgd_t h, void* stream) {
         const unsigned grid = grid_for(n4, 512, 4096);
         hipLaunchKernelGGL(fill_kernel, dim3(grid), dim3(512), 0, s, h->ms, 0.0f, n4, h->d);
     }
+    if (h->ctr) hipLaunchKernelGGL(counter_set_kernel, dim3(1), dim3(64), 0, s, h->ctr, 0u);
     h->stream = s;
     h->t = 0;
     h->fresh_at.assign((size_t)h->M, 0);
@@ -279,6 +287,7 @@ int dcasgd_push(dcasgd_t h, int worker, const void* grad, void* stream) {
     if (int rc = check_grad(h, grad)) return fail(h, rc);
     hipStream_t s = static_cast<hipStream_t>(stream);
     launch_push(h, worker, grad, h->pull_on_push, s);
+    advance_counter(h, 1, s);
     h->stream = s;
     h->t += 1;
     if (h->pull_on_push) h->fresh_at[(size_t)worker] = h->t;
@@ -307,6 +316,7 @@ int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads, 
         launch_batch(h, workers, grads, begin, end, s);
         begin = end;
     }
+    advance_counter(h, (uint32_t)K, s);
     h->stream = s;
     for (int k = 0; k < K; ++k) {
         h->t += 1;
@@ -334,7 +344,8 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
     float* row = h->bak + (size_t)worker * h->bak_stride;
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-    const uint32_t push_idx = (uint32_t)h->t;
+    // with a device-resident counter the kernel reads the push index itself
+    const uint32_t push_idx = h->ctr ? 0u : (uint32_t)h->t;
     hipStream_t s = static_cast<hipStream_t>(stream);
     with_bool(h->adaptive, [&](auto AD) {
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
@@ -345,12 +356,13 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
                                                   decltype(BF)::value, decltype(PL)::value,
                                                   decltype(IT)::value>),
                             grid, h->threads, s, h->hp, h->w, h->ms, row, hdiag, wstar, sigma, k0,
-                            k1, push_idx, n4, h->d);
+                            k1, push_idx, h->ctr, n4, h->d);
           });
         });
       });
      });
     });
+    advance_counter(h, 1, s);
     h->stream = s;
     h->t += 1;
     if (h->pull_on_push) h->fresh_at[(size_t)worker] = h->t;
@@ -385,6 +397,7 @@ int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat,
       });
      });
     });
+    advance_counter(h, (uint32_t)J, s);
     h->stream = s;
     h->t += (uint64_t)J;
     return launched(h);
@@ -438,6 +451,63 @@ int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream) {
                        h->d);
     h->hp.mu = mu;
     h->hp.vel = vel;
+    h->stream = s;
+    return launched(h);
+}
+
+int dcasgd_bind_counter(dcasgd_t h, uint32_t* counter, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (!counter) {
+        h->ctr = nullptr;
+        return DCASGD_OK;
+    }
+    if (!aligned(counter, 4)) return fail(h, DCASGD_EALIGN);
+    const size_t vb = h->d * 4;
+    if (overlaps(counter, 4, h->w, vb) ||
+        overlaps(counter, 4, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+        (h->ms && overlaps(counter, 4, h->ms, vb)) ||
+        (h->hp.vel && overlaps(counter, 4, h->hp.vel, vb)))
+        return fail(h, DCASGD_EINVAL);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(counter_set_kernel, dim3(1), dim3(64), 0, s, counter, (uint32_t)h->t);
+    h->ctr = counter;
+    h->stream = s;
+    return launched(h);
+}
+
+int dcasgd_set_step(dcasgd_t h, uint64_t t) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    h->t = t;
+    // which backups equal w is unknown after launches the host did not see
+    h->fresh_at.assign((size_t)h->M, ~(uint64_t)0);
+    return DCASGD_OK;
+}
+
+int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* wstar, float sigma,
+                       uint64_t seed, uint32_t offset, void* grad_out, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (worker < 0 || worker >= h->M || !hdiag || !wstar || !std::isfinite(sigma))
+        return fail(h, DCASGD_EINVAL);
+    if (h->d > ((size_t)1 << 34) || h->t + offset > 0xFFFFFFFFull) return fail(h, DCASGD_EINVAL);
+    if (int rc = check_grad(h, grad_out)) return fail(h, rc);
+    if (!aligned(hdiag, 16) || !aligned(wstar, 16)) return fail(h, DCASGD_EALIGN);
+    const size_t vb = h->d * 4, gb = grad_bytes(h);
+    if (overlaps(grad_out, gb, hdiag, vb) || overlaps(grad_out, gb, wstar, vb))
+        return fail(h, DCASGD_EINVAL);
+    const float* snap = h->bak + (size_t)worker * h->bak_stride;
+    const size_t n4 = h->d / 4;
+    const unsigned grid = grid_for(n4, 256, 0);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint32_t t_arg = h->ctr ? offset : (uint32_t)h->t + offset;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    with_bool(h->grad_bf16, [&](auto BF) {
+        hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, 1>), dim3(grid), dim3(256), 0, s,
+                           snap, hdiag, wstar, sigma, k0, k1, t_arg,
+                           static_cast<const uint32_t*>(h->ctr), grad_out, n4, h->d);
+    });
     h->stream = s;
     return launched(h);
 }
@@ -515,7 +585,7 @@ int dcasgd_synth_grad(const float* snap, const float* hdiag, const float* wstar,
         with_items(items, [&](auto IT) {
             hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, decltype(IT)::value>),
                                dim3(grid), dim3(threads), 0, s, snap, hdiag, wstar, sigma, k0, k1,
-                               push_idx, grad_out, n4, d);
+                               push_idx, static_cast<const uint32_t*>(nullptr), grad_out, n4, d);
         });
     });
     return hipGetLastError() == hipSuccess ? DCASGD_OK : DCASGD_EHIP;

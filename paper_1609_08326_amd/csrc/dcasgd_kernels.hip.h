@@ -606,12 +606,30 @@ __device__ __forceinline__ float synth_one(float snap, float h, float wstar, flo
     return pull_back + noise;
 }
 
+// The push index that keys the noise: a launch argument, or - when the server
+// keeps its push counter in device memory - that counter plus the argument,
+// read when the kernel runs, so a captured launch sequence can be replayed
+// and still draws fresh noise.
+__device__ __forceinline__ uint32_t push_index(uint32_t t_arg, const uint32_t* ctr) {
+    return ctr ? *ctr + t_arg : t_arg;
+}
+
+// The device-side push counter: set, and advance after pushes (one lane).
+__global__ void counter_set_kernel(uint32_t* ctr, uint32_t value) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *ctr = value;
+}
+__global__ void counter_add_kernel(uint32_t* ctr, uint32_t n) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *ctr = *ctr + n;
+}
+
 // g = h * (snap - wstar) + sigma * z, four parameters per Philox counter.
 template <bool BF16, int ITEMS>
 __global__ void __launch_bounds__(512)
 synth_grad_kernel(const float* __restrict__ snap, const float* __restrict__ hdiag,
                   const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
-                  uint32_t t, void* __restrict__ out, size_t n4, size_t d) {
+                  uint32_t t_arg, const uint32_t* __restrict__ ctr, void* __restrict__ out,
+                  size_t n4, size_t d) {
+    const uint32_t t = push_index(t_arg, ctr);
     const size_t tile_quads = (size_t)blockDim.x * ITEMS;
     const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
@@ -724,7 +742,8 @@ __global__ void __launch_bounds__(512)
 push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
                   float* __restrict__ bak, const float* __restrict__ hdiag,
                   const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
-                  uint32_t t, size_t n4, size_t d) {
+                  uint32_t t_arg, const uint32_t* __restrict__ ctr, size_t n4, size_t d) {
+    const uint32_t t = push_index(t_arg, ctr);
     const size_t tile_quads = (size_t)blockDim.x * ITEMS;
     const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
