@@ -105,6 +105,10 @@ def main() -> int:
     ap.add_argument("--fused-worker", action="store_true",
                     help="also time the worker+push fusion (dcasgd_push_synth) and report it "
                          "under 'fused_worker_path'; K=1 workloads only")
+    ap.add_argument("--graph", type=int, default=0, metavar="G",
+                    help="also capture a block of G arrivals (worker gradient + push each) into a "
+                         "HIP graph and time its replays, reported under 'graph_replay_path'; "
+                         "meant for the launch-bound 1 MB workloads, K=1 only")
     ap.add_argument("--no-events", action="store_true",
                     help="no per-kernel events at all (whole-path timing only)")
     ap.add_argument("--stream-events", action="store_true",
@@ -263,6 +267,44 @@ def main() -> int:
                                     "bytes_per_element_update": fbytes / wl.d,
                                     "note": "synthetic workload only: worker gradient formed in "
                                             "registers inside the push kernel"}
+    if args.graph > 0 and K == 1 and not sync:
+        # The push counter moves to device memory, so the captured launches keep
+        # drawing fresh noise on every replay; the block of arrivals repeats.
+        G = args.graph
+        block = [int(m) for m in arrivals[:G]]
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+
+        def run_block():
+            for m in block:
+                if args.fused_worker:
+                    sv.push_synth(m, hd, ws, wl.sigma, wl.seed)
+                else:
+                    sv.worker_grad(m, hd, ws, wl.sigma, wl.seed, gbuf[0])
+                    sv.push(m, gbuf[0])
+
+        with torch.cuda.stream(side):
+            sv.bind_counter()
+            run_block()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            run_block()
+        replays = max(1, -(-n_steps // G))
+        for _ in range(max(1, n_warm // G)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        ge = time.perf_counter() - t0
+        out["graph_replay_path"] = {"value": wl.d * G * replays / ge, "unit": "element-updates/s",
+                                    "us_per_arrival": 1e6 * ge / (G * replays),
+                                    "arrivals_per_graph": G, "replays": replays,
+                                    "note": ("worker fused into the push, " if args.fused_worker
+                                             else "worker gradient + fused push+pull per arrival, ")
+                                            + "launches replayed from one HIP graph"}
     if args.cpu_seconds > 0 and not sync:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(out), flush=True)
