@@ -81,3 +81,31 @@ def test_push_synth_equals_separate_launches():
     assert_same_bits(sv.w.cpu().numpy(), plain.w, "fused vs separate w")
     assert_same_bits(sv.ms.cpu().numpy(), plain.ms, "fused vs separate ms")
     assert_same_bits(sv.bak[:, : wl.d].cpu().numpy().ravel(), plain.bak.ravel(), "fused vs separate bak")
+
+
+def test_vector_longer_than_4_gib():
+    """d = 2^30 + 3: byte offsets inside one vector pass 2^32, the float4 group
+    index passes 2^28.  Worker-fused pushes and a separate worker + push, checked
+    on a sample that includes both ends of the vector."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = W.CONFIGS[2].replace(name="huge", d=(1 << 30) + 3, M=1, T=3)
+    say("huge vector d=%d" % wl.d)
+    hd_h, ws_h = wl.hdiag(), wl.wstar()
+    hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    sv = B.Server(torch.zeros(wl.d, device="cuda"), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
+                  wl.eps, pull_on_push=True)
+    sv.push_synth(0, hd, ws, wl.sigma, wl.seed)
+    sv.push_synth(0, hd, ws, wl.sigma, wl.seed)
+    g = torch.empty(wl.d, device="cuda")
+    B.synth_grad(sv.snapshot(0), hd, ws, wl.sigma, wl.seed, 2, g)
+    sv.push(0, g)
+    torch.cuda.synchronize()
+    idx = wl.sample_indices(100_000, edge=4096)
+    ii = torch.from_numpy(idx.astype(np.int64)).cuda()
+    ref = oracle_run(wl, hd_h, ws_h, np.zeros(3, dtype=np.int32), idx=idx, nthreads=16)
+    assert_same_bits(sv.w[ii].cpu().numpy(), ref.w(), "huge w")
+    assert_same_bits(sv.ms[ii].cpu().numpy(), ref.ms(), "huge ms")
+    assert_same_bits(sv.bak[0][ii].cpu().numpy(), ref.bak(0), "huge bak")
+    # nothing beyond the sample is left untouched: w moved everywhere h is not tiny
+    assert int((sv.w == 0).sum().item()) < wl.d // 1000
