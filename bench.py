@@ -178,15 +178,29 @@ def main() -> int:
     for i in range(n_warm):
         step(i, None)
     torch.cuda.synchronize()
-    if kernel_events:
-        sv.timing(True)
-    t0 = time.perf_counter()
-    for i in range(n_steps):
-        step(n_warm + i, ev[i] if stream_events else None)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    kernel_ms, kernel_launches = sv.timing_read() if kernel_events else (0.0, 0)
-    sv.timing(False)
+
+    def timed_region():
+        if kernel_events:
+            sv.timing(True)
+        t_start = time.perf_counter()
+        for i in range(n_steps):
+            step(n_warm + i, ev[i] if stream_events else None)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t_start
+        try:
+            ms, launches = sv.timing_read() if kernel_events else (0.0, 0)
+        except B.DcasgdError:
+            ms, launches = 0.0, 0
+        sv.timing(False)
+        return dt, ms, launches
+
+    elapsed, kernel_ms, kernel_launches = timed_region()
+    if kernel_events and (kernel_launches == 0 or not kernel_ms > 0.0):
+        # the runtime gave no times for launch-attached events: measure again
+        # with stream events around the kernels instead
+        kernel_events, stream_events = False, True
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_steps)]
+        elapsed, kernel_ms, kernel_launches = timed_region()
 
     updates = wl.d * K * n_steps
     value = updates / elapsed
