@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 VALU_PEAK_TLANE = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
-def algorithmic_bytes_per_update(wl) -> float:
+def algorithmic_bytes_per_update(wl, unfused: bool = False) -> float:
     """Bytes the method itself must move per element per applied push
     (fused push+pull): reads w, backup, gradient (+MeanSquare), writes w,
     backup (+MeanSquare).  Queue of K: w/MeanSquare once per queue."""
@@ -42,7 +42,8 @@ def algorithmic_bytes_per_update(wl) -> float:
     if wl.K > 1:
         per_queue = (16 if adaptive else 8) + wl.K * (g + 4 + 4)
         return per_queue / wl.K
-    return (4 + 4 + g + 4 + 4) + (8 if adaptive else 0)
+    # unfused: the separate pull reads w once more
+    return (4 + 4 + g + 4 + 4) + (8 if adaptive else 0) + (4 if unfused else 0)
 
 
 def read_profile(name: str, key: str = "traffic_bytes_per_launch"):
@@ -105,6 +106,9 @@ def main() -> int:
     ap.add_argument("--fused-worker", action="store_true",
                     help="also time the worker+push fusion (dcasgd_push_synth) and report it "
                          "under 'fused_worker_path'; K=1 workloads only")
+    ap.add_argument("--unfused", action="store_true",
+                    help="K=1 workloads: push and pull as two launches (24 + 8 bytes per update "
+                         "in the adaptive variant) instead of the fused one")
     ap.add_argument("--graph", type=int, default=0, metavar="G",
                     help="also capture a block of G arrivals (worker gradient + push each) into a "
                          "HIP graph and time its replays, reported under 'graph_replay_path'; "
@@ -139,7 +143,7 @@ def main() -> int:
     ws = torch.from_numpy(wl.wstar()).to(dev)
     w = torch.from_numpy(wl.w0()).to(dev)
     sv = B.Server(w, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps,
-                  grad_bf16=wl.grad_bf16, pull_on_push=not batched)
+                  grad_bf16=wl.grad_bf16, pull_on_push=not batched and not args.unfused)
     if args.threads or args.items or args.max_blocks or args.streaming >= 0:
         sv.set_launch(args.threads, args.items, args.max_blocks,
                       args.streaming if args.streaming >= 0 else 2)
@@ -172,6 +176,8 @@ def main() -> int:
             sv.push_batch(ms_, gbuf)
         else:
             sv.push(ms_[0], gbuf[0])
+            if args.unfused:
+                sv.pull(ms_[0])
         if rec:
             rec[2].record()
 
@@ -204,8 +210,10 @@ def main() -> int:
 
     updates = wl.d * K * n_steps
     value = updates / elapsed
-    bpu = algorithmic_bytes_per_update(wl)
-    kname = "sync_fold_J%d" % K if sync else "push_batch_K%d" % K if batched else "push_fused"
+    unfused = args.unfused and K == 1 and not sync
+    bpu = algorithmic_bytes_per_update(wl, unfused)
+    kname = ("sync_fold_J%d" % K if sync else "push_batch_K%d" % K if batched
+             else "push_then_pull" if unfused else "push_fused")
     out = {
         "metric": "element-updates/sec",
         "value": value,

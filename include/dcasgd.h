@@ -179,7 +179,7 @@ int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* 
                        float sigma, uint64_t seed, uint32_t offset, void* grad_out, void* stream);
 
 /*
- * Per-launch timing of the server-update kernels (push, push_batch,
+ * Per-launch timing of the server-update kernels (push, pull, push_batch,
  * push_synth, sync_fold).  While enabled, every such launch carries its own
  * start and stop HIP events, attached to the kernel itself, so their distance
  * is the kernel's execution time with no dispatch gap in it.  Events are host

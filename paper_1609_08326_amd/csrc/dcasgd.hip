@@ -146,8 +146,8 @@ void launch_pull(dcasgd_t h, int worker, hipStream_t s) {
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
     with_items(h->items, [&](auto IT) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            hipLaunchKernelGGL((pull_kernel<decltype(IT)::value, decltype(NT)::value>),
-                               dim3(grid), dim3(h->threads), 0, s, h->w, row, n4, h->d);
+            DCASGD_LAUNCH(h, (pull_kernel<decltype(IT)::value, decltype(NT)::value>), grid,
+                          h->threads, s, static_cast<const float*>(h->w), row, n4, h->d);
         });
     });
 }
