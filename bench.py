@@ -106,6 +106,9 @@ def main() -> int:
     ap.add_argument("--fused-worker", action="store_true",
                     help="also time the worker+push fusion (dcasgd_push_synth) and report it "
                          "under 'fused_worker_path'; K=1 workloads only")
+    ap.add_argument("--variant", choices=["a", "c"], default=None,
+                    help="override the workload's variant (c: constant lambda 0.04, a: adaptive "
+                         "lambda0 2, m 0.95, eps 1e-7) to time the other kernel at the same size")
     ap.add_argument("--unfused", action="store_true",
                     help="K=1 workloads: push and pull as two launches (24 + 8 bytes per update "
                          "in the adaptive variant) instead of the fused one")
@@ -131,6 +134,10 @@ def main() -> int:
     from paper_1609_08326_amd import workloads as W
 
     wl = W.get(args.workload)
+    if args.variant == "c":
+        wl = wl.replace(name=wl.name + "+c", mode=W.MODE_C, lambda0=0.04, ema_m=0.0, eps=0.0)
+    elif args.variant == "a":
+        wl = wl.replace(name=wl.name + "+a", mode=W.MODE_A, lambda0=2.0, ema_m=0.95, eps=1e-7)
     sync = wl.order == "sync"
     batched = wl.K > 1 and not sync
     K = wl.K
