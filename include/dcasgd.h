@@ -188,7 +188,8 @@ int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* 
  * dcasgd_timing(h, enable) switches it and forgets unread launches;
  * dcasgd_timing_read waits for the last timed launch, returns the summed
  * kernel time in milliseconds and the number of launches since the last read
- * (host pointers), and starts a new interval.
+ * (host pointers), and starts a new interval.  At most 65536 launches are
+ * timed between two reads; later ones run untimed.
  */
 int dcasgd_timing(dcasgd_t h, int enable);
 int dcasgd_timing_read(dcasgd_t h, double* total_ms, uint64_t* launches);

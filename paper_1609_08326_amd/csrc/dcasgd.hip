@@ -22,6 +22,9 @@ using namespace dcasgd;
 #ifndef DCASGD_BATCH_PIPE
 #define DCASGD_BATCH_PIPE 1
 #endif
+// Launches that can be timed between two dcasgd_timing_read calls; further
+// ones run untimed, so an unread handle does not pile up events.
+#define DCASGD_MAX_TIMED 65536
 
 struct dcasgd_server {
     size_t d = 0;
@@ -93,6 +96,7 @@ inline unsigned grid_for(size_t n4, size_t per_block, int max_blocks) {
 
 // Two events of their own for the next timed launch (created on demand, reused).
 inline bool next_event_pair(dcasgd_t h, hipEvent_t* start, hipEvent_t* stop) {
+    if (h->timing_used >= 2 * (size_t)DCASGD_MAX_TIMED) return false;   // unread backlog full
     while (h->timing_events.size() < h->timing_used + 2) {
         hipEvent_t e = nullptr;
         if (hipEventCreate(&e) != hipSuccess) return false;
