@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
         L.oracle_set_ms.restype = None
         L.oracle_get_bak.argtypes = [vp, C.c_int, f32p]
         L.oracle_get_bak.restype = C.c_int
+        L.oracle_grad_sqnorms.argtypes = [f32p, C.c_int, C.c_size_t, C.POINTER(C.c_double)]
+        L.oracle_grad_sqnorms.restype = None
         L.oracle_sync_fold.argtypes = [vp, f32p, C.c_int, C.c_float]
         L.oracle_sync_fold.restype = C.c_int
         L.oracle_synth_grad.argtypes = [f32p, f32p, f32p, C.c_float, C.c_uint64, C.c_uint32,
@@ -127,6 +129,16 @@ def bf16_rne(x) -> np.ndarray:
     x = _f32(x).ravel()
     out = np.zeros(x.size, dtype=np.uint16)
     lib().oracle_bf16_rne(_fp(x), out.ctypes.data_as(C.POINTER(C.c_uint16)), x.size)
+    return out
+
+
+def grad_sqnorms(grads) -> np.ndarray:
+    """Squared norms of the rows of ``grads`` (J x n float32), accumulated in double."""
+    g = np.ascontiguousarray(grads, dtype=np.float32)
+    assert g.ndim == 2
+    out = np.zeros(g.shape[0], dtype=np.float64)
+    lib().oracle_grad_sqnorms(_fp(g), int(g.shape[0]), int(g.shape[1]),
+                              out.ctypes.data_as(C.POINTER(C.c_double)))
     return out
 
 

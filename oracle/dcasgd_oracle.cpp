@@ -37,8 +37,9 @@
 //   * (1 - m) of Eq. 18 is formed once, in binary32.
 //   * the compensation term is grouped (lambda * g*g) * (w - w_bak): the
 //     diagonal Hessian estimate lambda g.g of Section 4 is formed first.
-//   * in the synchronous fold the order of the J gradients is the caller's
-//     (the supplement only suggests ordering by distance from w_t); lambda
+//   * in the synchronous fold the order of the J gradients is the caller's;
+//     the supplement suggests ordering by the distance from w_t, read here as
+//     ascending gradient norm (a helper computes the norms, in double); lambda
 //     may be the adaptive one, MeanSquare then advances once per gradient;
 //     eta_hat/J is formed once in binary32.
 //   * momentum: the paper names momentum variants (footnote, Section 6)
@@ -403,6 +404,21 @@ int oracle_get_bak(void* h, int worker, float* out) {
 void oracle_set_ms(void* h, const float* in) {
     Server& sv = *static_cast<Server*>(h);
     sv.ms.assign(in, in + sv.n);
+}
+
+// Squared Euclidean norms of J gradients (g: J*n floats), in double.  With a
+// common step the distance |wt - w_t| that gradient j alone would produce is
+// proportional to |g_j|, which is the quantity the supplement proposes to
+// order the fold by (smallest first).
+void oracle_grad_sqnorms(const float* g, int J, size_t n, double* out) {
+    for (int j = 0; j < J; ++j) {
+        double acc = 0.0;
+        for (size_t i = 0; i < n; ++i) {
+            const double x = (double)g[(size_t)j * n + i];
+            acc += x * x;
+        }
+        out[j] = acc;
+    }
 }
 
 // Synchronous delay-compensated fold of J gradients (g: J*n floats, gradient

@@ -105,3 +105,39 @@ def test_adaptive_fold_advances_mean_square_per_gradient():
     assert float(sv.ms()[0]) == ms
     assert abs(float(sv.w()[0]) - w) < 1e-6
     assert sv.t == 2
+
+
+def test_grad_sqnorms_against_a_library_dot_product():
+    rng = np.random.default_rng(6)
+    g = (rng.standard_normal((5, 100003)) * np.array([[1e-3], [1.0], [30.0], [1e-6], [0.2]])).astype(F32)
+    got = oracle.grad_sqnorms(g)
+    g64 = g.astype(np.float64)
+    ref = np.einsum("ji,ji->j", g64, g64)
+    assert np.all(np.abs(got - ref) <= 1e-12 * ref)
+    # exact on small integers, and the order it induces
+    h = np.array([[3, 4, 0], [1, 1, 1], [0, 0, 2]], dtype=F32)
+    assert oracle.grad_sqnorms(h).tolist() == [25.0, 3.0, 4.0]
+    assert np.argsort(oracle.grad_sqnorms(h), kind="stable").tolist() == [1, 2, 0]
+
+
+def test_smallest_first_keeps_the_running_model_closer_to_the_snapshot():
+    """The reason the supplement gives for an order: applying the small
+    gradients first keeps |wt^j - w_t| smaller along the way (checked on the
+    distances themselves, with lambda = 0 so that the steps are the gradients)."""
+    rng = np.random.default_rng(7)
+    n, J = 256, 6
+    g = (rng.standard_normal((J, n)) * rng.uniform(0.1, 3.0, (J, 1))).astype(F32)
+    order = np.argsort(oracle.grad_sqnorms(g), kind="stable")
+
+    def path_distances(rows):
+        w0 = np.zeros(n, dtype=F32)
+        out = []
+        for j in range(1, J + 1):
+            sv = oracle.Server(w0, 1, 0.0, 0.0, MODE_C)
+            sv.sync_fold(rows[:j], 0.1 * j)        # step 0.1 per gradient
+            out.append(float(np.linalg.norm(sv.w().astype(np.float64))))
+        return np.array(out)
+
+    asc, desc = path_distances(g[order]), path_distances(g[order[::-1]])
+    assert np.all(asc[:-1] <= desc[:-1] + 1e-9)
+    assert abs(asc[-1] - desc[-1]) < 1e-4            # same end point without compensation
