@@ -39,7 +39,7 @@
 //     diagonal Hessian estimate lambda g.g of Section 4 is formed first.
 //   * in the synchronous fold the order of the J gradients is the caller's;
 //     the supplement suggests ordering by the distance from w_t, read here as
-//     ascending gradient norm (a helper computes the norms, in double); lambda
+//     ascending gradient norm (a helper computes the squared norms); lambda
 //     may be the adaptive one, MeanSquare then advances once per gradient;
 //     eta_hat/J is formed once in binary32.
 //   * momentum: the paper names momentum variants (footnote, Section 6)
@@ -406,18 +406,22 @@ void oracle_set_ms(void* h, const float* in) {
     sv.ms.assign(in, in + sv.n);
 }
 
-// Squared Euclidean norms of J gradients (g: J*n floats), in double.  With a
-// common step the distance |wt - w_t| that gradient j alone would produce is
-// proportional to |g_j|, which is the quantity the supplement proposes to
-// order the fold by (smallest first).
+// Squared Euclidean norms of J gradients (g: J*n floats).  With a common step
+// the distance |wt - w_t| that gradient j alone would produce is proportional
+// to |g_j|, which is the quantity the supplement proposes to order the fold
+// by (smallest first).  The value meant is the real number sum g_i^2: each
+// square is exact in the 64-bit significand of long double and the running
+// sum is kept there, so the double returned is the true value to within a few
+// units of 2^-53 even for tens of millions of terms.
 void oracle_grad_sqnorms(const float* g, int J, size_t n, double* out) {
+    static_assert(sizeof(long double) > sizeof(double), "needs an extended accumulator");
     for (int j = 0; j < J; ++j) {
-        double acc = 0.0;
+        long double acc = 0.0L;
         for (size_t i = 0; i < n; ++i) {
-            const double x = (double)g[(size_t)j * n + i];
+            const long double x = (long double)g[(size_t)j * n + i];
             acc += x * x;
         }
-        out[j] = acc;
+        out[j] = (double)acc;
     }
 }
 

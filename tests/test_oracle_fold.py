@@ -113,7 +113,13 @@ def test_grad_sqnorms_against_a_library_dot_product():
     got = oracle.grad_sqnorms(g)
     g64 = g.astype(np.float64)
     ref = np.einsum("ji,ji->j", g64, g64)
-    assert np.all(np.abs(got - ref) <= 1e-12 * ref)
+    assert np.all(np.abs(got - ref) <= 1e-13 * ref)
+    # against exact rational arithmetic on a shorter vector
+    from fractions import Fraction
+    short = g[:, :2000]
+    exact = [sum(Fraction(float(x)) ** 2 for x in row) for row in short]
+    for a, e in zip(oracle.grad_sqnorms(short), exact):
+        assert abs(Fraction(float(a)) - e) <= e * Fraction(1, 2 ** 52)
     # exact on small integers, and the order it induces
     h = np.array([[3, 4, 0], [1, 1, 1], [0, 0, 2]], dtype=F32)
     assert oracle.grad_sqnorms(h).tolist() == [25.0, 3.0, 4.0]
