@@ -115,10 +115,29 @@ int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads,
  * i.e. the push rule above with eta = eta_hat/J (formed once in binary32) and
  * b = w_t for every j; in MODE_A MeanSquare advances once per gradient.  One
  * pass per element with w_t, w and ms in registers; backups are not touched;
- * t advances by J.  The order heuristic the supplement mentions (by distance
- * from w_t) is left to the caller.
+ * t advances by J.  The order is the caller's; dcasgd_sync_fold_ordered below
+ * applies the supplement's order heuristic.
  */
 int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream);
+
+/*
+ * The same fold with the order the supplement suggests at the end of that
+ * section: the gradients whose running model stays closest to w_t go first,
+ * taken here as ascending Euclidean norm of g_j (ties: the caller's order; a
+ * gradient whose norm is NaN goes last).  Three launches on the stream: the
+ * squared norms (binary64 accumulation of the exact squares, a fixed
+ * summation tree, so a repeated call gives the same bits), the ranking, and
+ * the fold of dcasgd_sync_fold over the ranked list; no host round trip.
+ * workspace: device memory, DCASGD_FOLD_WS_BYTES bytes, 256-byte aligned,
+ * caller-owned, overlapping none of the server's vectors or the gradients;
+ * contents on entry are irrelevant.  After the call has run it holds, from its
+ * start: 16 doubles, |g_j|^2 in the caller's numbering (entries < J valid);
+ * at byte 128: 16 int32, perm[r] = caller's index of the r-th gradient folded.
+ * Two calls that share a workspace must not overlap in time.
+ */
+#define DCASGD_FOLD_WS_BYTES 262656
+int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float eta_hat,
+                             void* workspace, void* stream);
 
 /*
  * Algorithm 2, "pull request": w_bak(worker) <- w, enqueued on the stream of

@@ -19,6 +19,7 @@ MODE_A = 1
 GRAD_BF16 = 1 << 4
 PULL_ON_PUSH = 1 << 5
 MAX_K = 16
+FOLD_WS_BYTES = 262656
 
 OK, EINVAL, EALIGN, ESTATE, EHIP = 0, -1, -2, -3, -4
 
@@ -34,6 +35,8 @@ _PROTOTYPES = {
                                     C.c_int, C.c_void_p]),
     "dcasgd_sync_fold": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
                                    C.c_void_p]),
+    "dcasgd_sync_fold_ordered": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
+                                           C.c_void_p, C.c_void_p]),
     "dcasgd_push_synth": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
                                     C.c_uint64, C.c_void_p]),
     "dcasgd_pull": (C.c_void_p, [C.c_void_p, C.c_int]),
@@ -233,14 +236,38 @@ class Server:
                                         float(sigma), int(seed), _stream_ptr(stream)),
                "dcasgd_push_synth")
 
-    def sync_fold(self, grads: Sequence, eta_hat: float, stream=None) -> None:
-        """Fold J same-snapshot gradients into w (the supplement's synchronous variant)."""
+    def sync_fold(self, grads: Sequence, eta_hat: float, stream=None, workspace=None) -> None:
+        """Fold J same-snapshot gradients into w (the supplement's synchronous variant).
+        With a workspace (see fold_workspace) the gradients are ranked by norm on the
+        device first and folded smallest first; otherwise in the order given."""
         J = len(grads)
         for g in grads:
             assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
         ga = (C.c_void_p * J)(*[g.data_ptr() for g in grads])
-        _check(load().dcasgd_sync_fold(self._h, ga, J, float(eta_hat), _stream_ptr(stream)),
-               "dcasgd_sync_fold")
+        if workspace is None:
+            _check(load().dcasgd_sync_fold(self._h, ga, J, float(eta_hat), _stream_ptr(stream)),
+                   "dcasgd_sync_fold")
+            return
+        assert workspace.is_cuda and workspace.is_contiguous()
+        assert workspace.numel() * workspace.element_size() >= FOLD_WS_BYTES
+        _check(load().dcasgd_sync_fold_ordered(self._h, ga, J, float(eta_hat),
+                                               workspace.data_ptr(), _stream_ptr(stream)),
+               "dcasgd_sync_fold_ordered")
+
+    @staticmethod
+    def fold_workspace(device="cuda"):
+        """Device buffer of the size dcasgd_sync_fold_ordered asks for."""
+        import torch
+        return torch.empty(FOLD_WS_BYTES // 8, dtype=torch.float64, device=device)
+
+    @staticmethod
+    def fold_order(workspace, J: int):
+        """(squared norms, permutation) the last ordered fold left in its workspace;
+        the caller synchronises first."""
+        import torch
+        sq = workspace[:J].cpu().numpy().copy()
+        perm = workspace.view(torch.int32)[32:32 + J].cpu().numpy().copy()
+        return sq, perm
 
     def pull(self, worker: int):
         """Refresh worker's backup from w and return it (a view of row `worker`)."""

@@ -373,7 +373,11 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
     return launched(h);
 }
 
-int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream) {
+// Both fold entry points: with a workspace the gradients are first ranked by
+// norm on the device and folded in that order, without one the caller's order
+// stands.
+static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
+                     FoldWorkspace* ws, bool ordered, void* stream) {
     if (!h) return DCASGD_EINVAL;
     if (!h->ready) return fail(h, DCASGD_ESTATE);
     if (!grads || J < 1 || J > DCASGD_MAX_K || !std::isfinite(eta_hat))
@@ -384,19 +388,48 @@ int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat,
         if (int rc = check_grad(h, grads[j])) return fail(h, rc);
         a.grad[j] = grads[j];
     }
+    if (ordered) {
+        if (!ws) return fail(h, DCASGD_EINVAL);
+        if (!aligned(ws, 256)) return fail(h, DCASGD_EALIGN);
+        const size_t wb = sizeof(FoldWorkspace);
+        if (overlaps(ws, wb, h->w, h->d * 4) ||
+            overlaps(ws, wb, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+            (h->ms && overlaps(ws, wb, h->ms, h->d * 4)) ||
+            (h->hp.vel && overlaps(ws, wb, h->hp.vel, h->d * 4)) ||
+            (h->ctr && overlaps(ws, wb, h->ctr, 4)))
+            return fail(h, DCASGD_EINVAL);
+        for (int j = 0; j < J; ++j)
+            if (overlaps(ws, wb, grads[j], grad_bytes(h))) return fail(h, DCASGD_EINVAL);
+    }
     Hyper hp = h->hp;
     hp.eta = eta_hat / (float)J;            // per-gradient step, formed once in binary32
     const size_t n4 = h->d / 4;
     const int threads = h->batch_threads;
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (ordered) {
+        const int cap = (h->max_blocks > 0 && h->max_blocks < FOLD_WS_BLOCKS) ? h->max_blocks
+                                                                              : FOLD_WS_BLOCKS;
+        const unsigned nblocks = grid_for(n4, 256, cap);
+        with_bool(h->grad_bf16, [&](auto BF) {
+          with_bool(h->streaming != 0, [&](auto NT) {
+            DCASGD_LAUNCH(h, (grad_sqnorm_kernel<decltype(BF)::value, decltype(NT)::value, 4>),
+                          nblocks, 256, s, a, ws, n4, h->d);
+          });
+        });
+        DCASGD_LAUNCH(h, fold_order_kernel, 1, 256, s, a, ws, (int)nblocks);
+    }
     with_bool(h->adaptive, [&](auto AD) {
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
+          with_bool(ordered, [&](auto OR) {
             DCASGD_LAUNCH(h, (sync_fold_kernel<decltype(AD)::value, decltype(MO)::value,
-                                               decltype(BF)::value, 4, decltype(NT)::value>),
-                          grid, threads, s, hp, h->w, h->ms, a, n4, h->d);
+                                               decltype(BF)::value, 4, decltype(NT)::value,
+                                               decltype(OR)::value>),
+                          grid, threads, s, hp, h->w, h->ms, a,
+                          static_cast<const FoldWorkspace*>(ws), n4, h->d);
+          });
         });
       });
      });
@@ -405,6 +438,16 @@ int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat,
     h->stream = s;
     h->t += (uint64_t)J;
     return launched(h);
+}
+
+int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream) {
+    return fold_impl(h, grads, J, eta_hat, nullptr, false, stream);
+}
+
+int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float eta_hat,
+                             void* workspace, void* stream) {
+    static_assert(sizeof(FoldWorkspace) == DCASGD_FOLD_WS_BYTES, "header and kernels agree");
+    return fold_impl(h, grads, J, eta_hat, static_cast<FoldWorkspace*>(workspace), true, stream);
 }
 
 const float* dcasgd_pull(dcasgd_t h, int worker) {

@@ -404,9 +404,27 @@ struct FoldArgs {
     int J;
 };
 
+// Workspace of the ordered fold (device memory, caller-owned).  The first
+// launch leaves one partial sum of squares per block and gradient in
+// `partial`; the second adds them up in a fixed order (so the result does not
+// depend on scheduling), ranks the gradients and leaves the squared norms, the
+// permutation and the gradient pointers in fold order.
+constexpr int FOLD_WS_BLOCKS = 2048;
+struct FoldWorkspace {
+    double sqnorm[16];          // |g_j|^2 in the caller's numbering
+    int perm[16];               // perm[r] = caller's index of the r-th gradient folded
+    int reserved0[16];
+    const void* ordered[16];    // grad[perm[r]]
+    double reserved1[16];
+    double partial[16][FOLD_WS_BLOCKS];
+};
+static_assert(sizeof(FoldWorkspace) == 512 + 16 * FOLD_WS_BLOCKS * 8, "documented layout");
+
+// gp: the J gradient pointers in fold order, either the launch arguments
+// themselves or the list the ordering kernel left in device memory.
 template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool CHECKED>
 __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w,
-                                          float* __restrict__ ms, const FoldArgs& a,
+                                          float* __restrict__ ms, const void* const* gp, int J,
                                           size_t q, size_t n4) {
     if (CHECKED && q >= n4) return;
     const f32x4 anchor = load4<false>(w, q);
@@ -414,16 +432,16 @@ __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
     f32x4 V = load_vel4<MOM>(hp, q);
-    const int full = (a.J / KC) * KC;
+    const int full = (J / KC) * KC;
     for (int j0 = 0; j0 < full; j0 += KC) {
         f32x4 G[KC];
 #pragma unroll
-        for (int jj = 0; jj < KC; ++jj) G[jj] = load_grad4<BF16, NT>(a.grad[j0 + jj], q);
+        for (int jj = 0; jj < KC; ++jj) G[jj] = load_grad4<BF16, NT>(gp[j0 + jj], q);
 #pragma unroll
         for (int jj = 0; jj < KC; ++jj) apply_push4<ADAPTIVE, MOM>(hp, G[jj], anchor, W, S, V);
     }
-    for (int j = full; j < a.J; ++j) {
-        const f32x4 g = load_grad4<BF16, NT>(a.grad[j], q);
+    for (int j = full; j < J; ++j) {
+        const f32x4 g = load_grad4<BF16, NT>(gp[j], q);
         apply_push4<ADAPTIVE, MOM>(hp, g, anchor, W, S, V);
     }
     store4<false>(w, q, W);
@@ -431,17 +449,19 @@ __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w
     store_vel4<MOM>(hp, q, V);
 }
 
-template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool ORD>
 __global__ void __launch_bounds__(256)
 sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldArgs a,
-                 size_t n4, size_t d) {
+                 const FoldWorkspace* __restrict__ ws, size_t n4, size_t d) {
+    const void* const* gp = a.grad;
+    if constexpr (ORD) gp = ws->ordered;
     const size_t ntiles = (n4 + blockDim.x - 1) / blockDim.x;
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t q = tile * blockDim.x + threadIdx.x;
         if ((tile + 1) * blockDim.x <= n4)
-            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, false>(hp, w, ms, a, q, n4);
+            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, false>(hp, w, ms, gp, a.J, q, n4);
         else
-            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, true>(hp, w, ms, a, q, n4);
+            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, true>(hp, w, ms, gp, a.J, q, n4);
     }
     if (blockIdx.x == 0) {
         const size_t i = 4 * n4 + threadIdx.x;
@@ -452,11 +472,117 @@ sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldAr
             if constexpr (ADAPTIVE) si = ms[i];
             float vi = load_vel1<MOM>(hp, i);
             for (int j = 0; j < a.J; ++j)
-                apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(a.grad[j], i), anchor, wi, si, vi);
+                apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(gp[j], i), anchor, wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
             store_vel1<MOM>(hp, i, vi);
         }
+    }
+}
+
+// ---- fold order (supplement: fold in increasing distance from w_t) ----------------
+// Distance read as the gradient's own norm.  First launch: every block walks
+// its tiles once, holding one double accumulator per gradient and lane (the
+// square of a binary32 value is exact in binary64, so the only roundings are
+// those of the additions), then reduces over the block in a fixed order and
+// writes its J partial sums.  Pure read traffic: J gradients, once.
+template <bool BF16, bool NT, int KC>
+__global__ void __launch_bounds__(256)
+grad_sqnorm_kernel(FoldArgs a, FoldWorkspace* __restrict__ ws, size_t n4, size_t d) {
+    __shared__ double wave_sum[4][16];
+    double acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0;
+    const size_t ntiles = (n4 + blockDim.x - 1) / blockDim.x;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t q = tile * blockDim.x + threadIdx.x;
+        if (q >= n4) continue;
+#pragma unroll
+        for (int j0 = 0; j0 < 16; j0 += KC) {
+            if (j0 < a.J) {
+                f32x4 G[KC];
+#pragma unroll
+                for (int jj = 0; jj < KC; ++jj) {
+                    G[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (j0 + jj < a.J) G[jj] = load_grad4<BF16, NT>(a.grad[j0 + jj], q);
+                }
+#pragma unroll
+                for (int jj = 0; jj < KC; ++jj) {
+                    const double x = (double)G[jj].x, y = (double)G[jj].y;
+                    const double z = (double)G[jj].z, u = (double)G[jj].w;
+                    double s = acc[j0 + jj];
+                    s = __builtin_fma(x, x, s);
+                    s = __builtin_fma(y, y, s);
+                    s = __builtin_fma(z, z, s);
+                    s = __builtin_fma(u, u, s);
+                    acc[j0 + jj] = s;
+                }
+            }
+        }
+    }
+    if (blockIdx.x == 0) {
+        const size_t i = 4 * n4 + threadIdx.x;
+        if (i < d) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (j < a.J) {
+                    const double x = (double)load_grad1<BF16>(a.grad[j], i);
+                    acc[j] = __builtin_fma(x, x, acc[j]);
+                }
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        if (j < a.J) {
+            double s = acc[j];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+            if (lane == 0) wave_sum[wave][j] = s;
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < a.J) {
+        double s = wave_sum[0][threadIdx.x];
+        for (int v = 1; v < (int)(blockDim.x >> 6); ++v) s += wave_sum[v][threadIdx.x];
+        ws->partial[threadIdx.x][blockIdx.x] = s;
+    }
+}
+
+// Second launch, one block of 256: adds the per-block partial sums of each
+// gradient in a fixed order, then ranks the gradients by (squared norm, index)
+// with a NaN counted as +infinity, so that the ranks always form a
+// permutation; rank r receives caller's index perm[r] and its pointer.
+__global__ void __launch_bounds__(256)
+fold_order_kernel(FoldArgs a, FoldWorkspace* __restrict__ ws, int nblocks) {
+    __shared__ double red[256];
+    __shared__ double key[16];
+    const int t = threadIdx.x;
+    for (int j = 0; j < a.J; ++j) {
+        double s = 0.0;
+        for (int b = t; b < nblocks; b += 256) s += ws->partial[j][b];
+        red[t] = s;
+        __syncthreads();
+        for (int off = 128; off > 0; off >>= 1) {
+            if (t < off) red[t] += red[t + off];
+            __syncthreads();
+        }
+        if (t == 0) {
+            const double total = red[0];
+            ws->sqnorm[j] = total;
+            key[j] = (total != total) ? __builtin_huge_val() : total;
+        }
+        __syncthreads();
+    }
+    if (t < a.J) {
+        const double mine = key[t];
+        int rank = 0;
+        for (int k = 0; k < a.J; ++k) {
+            const double other = key[k];
+            rank += (other < mine || (other == mine && k < t)) ? 1 : 0;
+        }
+        ws->perm[rank] = t;
+        ws->ordered[rank] = a.grad[t];
     }
 }
 
