@@ -121,6 +121,9 @@ def main() -> int:
     ap.add_argument("--stream-events", action="store_true",
                     help="additionally record stream events between the kernels of a step and "
                          "report their intervals (adds a dispatch gap per event)")
+    ap.add_argument("--ordered", action="store_true",
+                    help="fold workload: after the timed region, time the same steps again "
+                         "with the gradients ranked by norm on the device before each fold")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU oracle sample length; 0 skips the baseline")
     args = ap.parse_args()
@@ -296,6 +299,39 @@ def main() -> int:
                                     "bytes_per_element_update": fbytes / wl.d,
                                     "note": "synthetic workload only: worker gradient formed in "
                                             "registers inside the push kernel"}
+    if args.ordered and sync:
+        # norms + ranking + fold over the ranked list: three launches per fold
+        fws = B.Server.fold_workspace(dev)
+
+        def ordered_step(i: int) -> None:
+            for j in range(K):
+                B.synth_grad(sv.w, hd, ws, wl.sigma, wl.seed, i * K + j, gbuf[j],
+                             threads=args.synth_threads, items=args.synth_items)
+            sv.sync_fold(gbuf, wl.eta * K, workspace=fws)
+
+        base_i = n_warm + n_steps
+        for i in range(n_warm):
+            ordered_step(base_i + i)
+        torch.cuda.synchronize()
+        if kernel_events:
+            sv.timing(True)
+        t0 = time.perf_counter()
+        for i in range(n_steps):
+            ordered_step(base_i + n_warm + i)
+        torch.cuda.synchronize()
+        oe = time.perf_counter() - t0
+        o_ms, o_launches = sv.timing_read() if kernel_events else (0.0, 0)
+        sv.timing(False)
+        gbytes = (2 if wl.grad_bf16 else 4) * wl.d * K
+        rep = {"value": updates / oe, "unit": "element-updates/s",
+               "ms_per_step": 1e3 * oe / n_steps,
+               "note": "squared norms, ranking and fold: three launches, no host round trip"}
+        if o_launches:
+            extra = o_ms / n_steps - out["roofline"]["avg_launch_ms"]
+            rep.update({"server_ms_per_fold": o_ms / n_steps, "launches_timed": o_launches,
+                        "norms_and_ranking_ms": extra,
+                        "norm_pass_algorithmic_GBs": gbytes / (extra * 1e-3) / 1e9})
+        out["ordered_fold_path"] = rep
     if args.graph > 0 and K == 1 and not sync:
         # The push counter moves to device memory, so the captured launches keep
         # drawing fresh noise on every replay; the block of arrivals repeats.

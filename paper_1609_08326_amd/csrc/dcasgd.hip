@@ -25,6 +25,9 @@ using namespace dcasgd;
 // Launches that can be timed between two dcasgd_timing_read calls; further
 // ones run untimed, so an unread handle does not pile up events.
 #define DCASGD_MAX_TIMED 65536
+#ifndef DCASGD_NORM_ITEMS
+#define DCASGD_NORM_ITEMS 4   // float4 groups a lane of the norm kernel has in flight
+#endif
 
 struct dcasgd_server {
     size_t d = 0;
@@ -42,6 +45,7 @@ struct dcasgd_server {
     int threads = 256, items = 2, max_blocks = 0;
     int batch_threads = 64;           // the queue kernel does 16x the work per lane: one wave per block
     int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything
+    int norm_blocks = 0;              // grid of the norm kernel, set on first use
     int last_error = DCASGD_OK;
     uint32_t* ctr = nullptr;          // optional device-resident copy of t (low 32 bits)
     // optional per-launch timing of the server-update kernels
@@ -408,16 +412,27 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (ordered) {
-        const int cap = (h->max_blocks > 0 && h->max_blocks < FOLD_WS_BLOCKS) ? h->max_blocks
-                                                                              : FOLD_WS_BLOCKS;
-        const unsigned nblocks = grid_for(n4, 256, cap);
+        if (h->norm_blocks == 0) {
+            // A pure read stream is fastest with few, long-lived blocks: two per
+            // compute unit measured best on MI355X (one 102 MB vector in 15 us).
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+                cus < 1)
+                return fail(h, DCASGD_EHIP);
+            h->norm_blocks = 2 * cus < FOLD_WS_BLOCKS ? 2 * cus : FOLD_WS_BLOCKS;
+        }
+        const int cap = (h->max_blocks > 0 && h->max_blocks < h->norm_blocks) ? h->max_blocks
+                                                                              : h->norm_blocks;
+        const unsigned nblocks = grid_for(n4, 256 * DCASGD_NORM_ITEMS, cap);
         with_bool(h->grad_bf16, [&](auto BF) {
           with_bool(h->streaming != 0, [&](auto NT) {
-            DCASGD_LAUNCH(h, (grad_sqnorm_kernel<decltype(BF)::value, decltype(NT)::value, 4>),
+            DCASGD_LAUNCH(h, (grad_sqnorm_kernel<decltype(BF)::value, decltype(NT)::value,
+                                                  DCASGD_NORM_ITEMS>),
                           nblocks, 256, s, a, ws, n4, h->d);
           });
         });
-        DCASGD_LAUNCH(h, fold_order_kernel, 1, 256, s, a, ws, (int)nblocks);
+        DCASGD_LAUNCH(h, fold_order_kernel, 1, 1024, s, a, ws, (int)nblocks);
     }
     with_bool(h->adaptive, [&](auto AD) {
      with_bool(h->hp.vel != nullptr, [&](auto MO) {

@@ -481,65 +481,59 @@ sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldAr
 }
 
 // ---- fold order (supplement: fold in increasing distance from w_t) ----------------
-// Distance read as the gradient's own norm.  First launch: every block walks
-// its tiles once, holding one double accumulator per gradient and lane (the
+// Distance read as the gradient's own norm.  First launch: the gradients are
+// walked one after the other, so that at any moment the whole chip streams
+// through one contiguous vector; a lane keeps one binary64 accumulator (the
 // square of a binary32 value is exact in binary64, so the only roundings are
-// those of the additions), then reduces over the block in a fixed order and
-// writes its J partial sums.  Pure read traffic: J gradients, once.
-template <bool BF16, bool NT, int KC>
+// those of the additions) and has ITEMS tiles in flight.  After each gradient
+// the wave adds up its lanes; at the end the block adds up its waves and
+// writes its J partial sums.  Every step has a fixed order.  Pure read
+// traffic: J gradients, once.
+template <bool BF16, bool NT, int ITEMS>
+__device__ __forceinline__ double lane_sum_of_squares(const void* __restrict__ g, size_t n4) {
+    double s = 0.0;
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t first = tile * tile_quads + threadIdx.x;
+        f32x4 G[ITEMS];
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            const size_t q = first + (size_t)k * blockDim.x;
+            G[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (q < n4) G[k] = load_grad4<BF16, NT>(g, q);
+        }
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            const double x = (double)G[k].x, y = (double)G[k].y;
+            const double z = (double)G[k].z, u = (double)G[k].w;
+            s = __builtin_fma(x, x, s);
+            s = __builtin_fma(y, y, s);
+            s = __builtin_fma(z, z, s);
+            s = __builtin_fma(u, u, s);
+        }
+    }
+    return s;
+}
+
+template <bool BF16, bool NT, int ITEMS>
 __global__ void __launch_bounds__(256)
 grad_sqnorm_kernel(FoldArgs a, FoldWorkspace* __restrict__ ws, size_t n4, size_t d) {
     __shared__ double wave_sum[4][16];
-    double acc[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) acc[j] = 0.0;
-    const size_t ntiles = (n4 + blockDim.x - 1) / blockDim.x;
-    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const size_t q = tile * blockDim.x + threadIdx.x;
-        if (q >= n4) continue;
-#pragma unroll
-        for (int j0 = 0; j0 < 16; j0 += KC) {
-            if (j0 < a.J) {
-                f32x4 G[KC];
-#pragma unroll
-                for (int jj = 0; jj < KC; ++jj) {
-                    G[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if (j0 + jj < a.J) G[jj] = load_grad4<BF16, NT>(a.grad[j0 + jj], q);
-                }
-#pragma unroll
-                for (int jj = 0; jj < KC; ++jj) {
-                    const double x = (double)G[jj].x, y = (double)G[jj].y;
-                    const double z = (double)G[jj].z, u = (double)G[jj].w;
-                    double s = acc[j0 + jj];
-                    s = __builtin_fma(x, x, s);
-                    s = __builtin_fma(y, y, s);
-                    s = __builtin_fma(z, z, s);
-                    s = __builtin_fma(u, u, s);
-                    acc[j0 + jj] = s;
-                }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int j = 0; j < a.J; ++j) {
+        const void* g = a.grad[j];
+        double s = lane_sum_of_squares<BF16, NT, ITEMS>(g, n4);
+        if (blockIdx.x == 0) {
+            const size_t i = 4 * n4 + threadIdx.x;
+            if (i < d) {
+                const double x = (double)load_grad1<BF16>(g, i);
+                s = __builtin_fma(x, x, s);
             }
         }
-    }
-    if (blockIdx.x == 0) {
-        const size_t i = 4 * n4 + threadIdx.x;
-        if (i < d) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                if (j < a.J) {
-                    const double x = (double)load_grad1<BF16>(a.grad[j], i);
-                    acc[j] = __builtin_fma(x, x, acc[j]);
-                }
-        }
-    }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        if (j < a.J) {
-            double s = acc[j];
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
-            if (lane == 0) wave_sum[wave][j] = s;
-        }
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+        if (lane == 0) wave_sum[wave][j] = s;
     }
     __syncthreads();
     if ((int)threadIdx.x < a.J) {
@@ -549,31 +543,27 @@ grad_sqnorm_kernel(FoldArgs a, FoldWorkspace* __restrict__ ws, size_t n4, size_t
     }
 }
 
-// Second launch, one block of 256: adds the per-block partial sums of each
-// gradient in a fixed order, then ranks the gradients by (squared norm, index)
-// with a NaN counted as +infinity, so that the ranks always form a
+// Second launch, one block of 16 waves: wave j adds the per-block partial sums
+// of gradient j (lane l takes blocks l, l+64, ... in that order, then the
+// lanes are added up), after which the gradients are ranked by (squared norm,
+// index) with a NaN counted as +infinity, so that the ranks always form a
 // permutation; rank r receives caller's index perm[r] and its pointer.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(1024)
 fold_order_kernel(FoldArgs a, FoldWorkspace* __restrict__ ws, int nblocks) {
-    __shared__ double red[256];
     __shared__ double key[16];
-    const int t = threadIdx.x;
-    for (int j = 0; j < a.J; ++j) {
+    const int lane = threadIdx.x & 63, j = threadIdx.x >> 6;
+    if (j < a.J) {
         double s = 0.0;
-        for (int b = t; b < nblocks; b += 256) s += ws->partial[j][b];
-        red[t] = s;
-        __syncthreads();
-        for (int off = 128; off > 0; off >>= 1) {
-            if (t < off) red[t] += red[t + off];
-            __syncthreads();
+        for (int b = lane; b < nblocks; b += 64) s += ws->partial[j][b];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+        if (lane == 0) {
+            ws->sqnorm[j] = s;
+            key[j] = (s != s) ? __builtin_huge_val() : s;
         }
-        if (t == 0) {
-            const double total = red[0];
-            ws->sqnorm[j] = total;
-            key[j] = (total != total) ? __builtin_huge_val() : total;
-        }
-        __syncthreads();
     }
+    __syncthreads();
+    const int t = threadIdx.x;
     if (t < a.J) {
         const double mine = key[t];
         int rank = 0;

@@ -24,11 +24,12 @@ def say(msg):
 
 def norm_tolerance(d):
     """Relative bound on |device - oracle| for a sum of d non-negative exact squares.
-    Device: a lane adds at most 4 terms per tile it visits (<= d/4/256/blocks + 1
-    tiles, at most ~13 at the sizes used here), then 6 shuffle steps, 3 wave sums,
-    up to 8 partials per lane and an 8-level tree: under 100 binary64 roundings on
+    Device: a lane adds 16 terms per tile of 1024 groups it visits (two blocks per
+    compute unit share the tiles: at most 13 tiles, 208 additions, at the sizes
+    used here), then 6 shuffle steps, 3 wave sums, and in the second launch up to
+    32 partials per lane and 6 more shuffle steps: under 256 binary64 roundings on
     any path, each on a partial sum below the total.  Oracle: d roundings at 2^-64."""
-    return 100 * 2.0 ** -53 + d * 2.0 ** -64
+    return 256 * 2.0 ** -53 + d * 2.0 ** -64
 
 
 def device_rows(g, bf16):
