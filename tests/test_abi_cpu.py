@@ -110,3 +110,25 @@ def test_product_path_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "dcasgd_oracle" not in text, f
+
+
+def test_header_is_plain_c_and_binding_matches_its_arity(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, and every
+    ctypes prototype must take as many arguments as the declaration it mirrors."""
+    import subprocess
+    from paper_1609_08326_amd import binding
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "dcasgd.h"\n'
+                   "int main(void) { return DCASGD_MAX_K == 16 && DCASGD_FOLD_WS_BYTES > 0 ? 0 : 1; }\n")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
+    text = open(os.path.join(ROOT, "include", "dcasgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    seen = 0
+    for name, args in re.findall(r"\b(dcasgd_[a-z_]+)\s*\(([^)]*)\)\s*;", text):
+        n = 0 if args.strip() in ("", "void") else args.count(",") + 1
+        assert len(binding._PROTOTYPES[name][1]) == n, name
+        seen += 1
+    assert seen == len(binding._PROTOTYPES)
+    assert binding.FOLD_WS_BYTES == int(re.search(r"#define DCASGD_FOLD_WS_BYTES (\d+)", text).group(1))
+    assert binding.MAX_K == int(re.search(r"#define DCASGD_MAX_K (\d+)", text).group(1))
