@@ -136,6 +136,8 @@ class Server:
                                     float(ema_m), float(eps))
         if not self._h:
             raise DcasgdError(EINVAL, "dcasgd_create")
+        self.vel = None                                 # velocity, once momentum is on
+        self.counter = None                             # device copy of t, once bound
         self.stride = (self.d + 63) // 64 * 64          # rows start 256-byte aligned
         self.w = w0
         self.bak = torch.empty((self.M, self.stride), dtype=torch.float32, device=w0.device)
