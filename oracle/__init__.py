@@ -67,6 +67,8 @@ def lib() -> C.CDLL:
         L.oracle_set_momentum.restype = None
         L.oracle_get_vel.argtypes = [vp, f32p]
         L.oracle_get_vel.restype = None
+        L.oracle_set_backup_bf16.argtypes = [vp, C.c_int]
+        L.oracle_set_backup_bf16.restype = None
         L.oracle_set_eta.argtypes = [vp, C.c_float]
         L.oracle_set_eta.restype = None
         L.oracle_push.argtypes = [vp, C.c_int, f32p]
@@ -179,6 +181,10 @@ class Server:
 
     def set_eta(self, eta: float) -> None:
         lib().oracle_set_eta(self._h, float(eta))
+
+    def set_backup_bf16(self, on: bool = True) -> None:
+        """Snapshots travel and are kept as bfloat16 (round to nearest even of w)."""
+        lib().oracle_set_backup_bf16(self._h, int(bool(on)))
 
     def set_momentum(self, mu: float) -> None:
         """Heavy-ball momentum on the compensated gradient; the velocity restarts at zero."""

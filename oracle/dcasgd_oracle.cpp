@@ -42,6 +42,8 @@
 //     ascending gradient norm (a helper computes the squared norms); lambda
 //     may be the adaptive one, MeanSquare then advances once per gradient;
 //     eta_hat/J is formed once in binary32.
+//   * bfloat16 snapshots (optional, not from the paper): the value handed to
+//     the worker and the value kept as w_bak(m) are the same rounded number.
 //   * momentum: the paper names momentum variants (footnote, Section 6)
 //     without a formula.  Implemented as a proposal, the classical heavy
 //     ball on the compensated gradient: v <- mu*v + g_dc, w <- w - eta*v, one
@@ -188,6 +190,7 @@ struct Server {
     uint64_t t = 0;        // pushes applied so far
     std::vector<float> w, ms, vel;
     std::vector<std::vector<float>> bak;
+    int bak_bf16 = 0;      // 1: a pull hands out (and the server keeps) w rounded to bfloat16
 };
 
 // The delay-compensated gradient of Eq. 4.1 with lambda_t = lambda_0, one element.
@@ -242,8 +245,16 @@ void push_range(Server& sv, int m, const float* g, size_t lo, size_t hi) {
 }
 
 // Algorithm 2, "pull request": w_bak(m) <- w_t, elements [lo, hi).
+// With bfloat16 snapshots the worker receives round-to-nearest-even(w) and the
+// server keeps exactly that value as w_bak(m): the gradient that comes back was
+// taken at the rounded point, so w - w_bak(m) is still the true displacement
+// from where the gradient was computed.  bak holds the widened value.
 void pull_range(Server& sv, int m, size_t lo, size_t hi) {
-    for (size_t i = lo; i < hi; ++i) sv.bak[m][i] = sv.w[i];
+    for (size_t i = lo; i < hi; ++i) {
+        float v = sv.w[i];
+        if (sv.bak_bf16) v = bf16_widen(bf16_rne(v));
+        sv.bak[m][i] = v;
+    }
 }
 
 // Supplement, last section: fold J gradients g[0..J) (each n floats, all taken
@@ -363,6 +374,17 @@ void oracle_set_momentum(void* h, float mu) {
 void oracle_get_vel(void* h, float* out) {
     Server& sv = *static_cast<Server*>(h);
     if (sv.momentum) std::memcpy(out, sv.vel.data(), sv.n * sizeof(float));
+}
+
+// Snapshot storage variant (not from the paper, which only notes that the
+// backups cost memory): bfloat16 backups.  Switching it on rounds the backups
+// held at that moment, as if each worker had pulled in the new format.
+void oracle_set_backup_bf16(void* h, int on) {
+    Server& sv = *static_cast<Server*>(h);
+    sv.bak_bf16 = on ? 1 : 0;
+    if (!on) return;
+    for (int m = 0; m < sv.M; ++m)
+        for (size_t i = 0; i < sv.n; ++i) sv.bak[m][i] = bf16_widen(bf16_rne(sv.bak[m][i]));
 }
 
 // Learning-rate schedule (Section 6 divides eta by ten at fixed epochs).
