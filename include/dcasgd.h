@@ -41,7 +41,8 @@ enum {
     DCASGD_MODE_C       = 0,       /* lambda_t = lambda0 (Section 6, "DC-ASGD-c")          */
     DCASGD_MODE_A       = 1,       /* lambda_t = lambda0/sqrt(MeanSquare(t)+eps), Eq. 18   */
     DCASGD_GRAD_BF16    = 1 << 4,  /* pushed gradients are bfloat16 (2 bytes per element)  */
-    DCASGD_PULL_ON_PUSH = 1 << 5   /* every push also refreshes the pusher's backup        */
+    DCASGD_PULL_ON_PUSH = 1 << 5,  /* every push also refreshes the pusher's backup        */
+    DCASGD_BAK_BF16     = 1 << 6   /* snapshots are handed out and kept as bfloat16        */
 };
 
 enum {
@@ -70,10 +71,18 @@ int dcasgd_destroy(dcasgd_t h);
 
 /*
  * Attach caller-owned device memory: w[d] (global model), bak (M rows of
- * bak_stride floats; row m is w_bak(m) of Algorithm 2), ms[d] (MeanSquare of
+ * bak_stride elements; row m is w_bak(m) of Algorithm 2), ms[d] (MeanSquare of
  * Eq. 18; may be NULL in MODE_C).  The ranges must not overlap.
+ * Backup elements are float32, bak_stride a multiple of 4.  With
+ * DCASGD_BAK_BF16 (a storage variant, not from the paper, which only remarks
+ * that the backups cost memory) they are bfloat16 and bak_stride is a multiple
+ * of 8: a pull stores round-to-nearest-even of w, the worker receives that
+ * rounded snapshot, and the next push of that worker is compensated against
+ * the very same number, so w - w_bak(m) is still the displacement from the
+ * point the gradient was taken at.  Half the backup memory and pull traffic;
+ * set_launch's streaming level is not honoured by the single-push kernel then.
  */
-int dcasgd_bind(dcasgd_t h, float* w, float* bak, size_t bak_stride, float* ms);
+int dcasgd_bind(dcasgd_t h, float* w, void* bak, size_t bak_stride, float* ms);
 
 /*
  * Algorithm 2, "Initialize": w_bak(m) <- w for every m, MeanSquare <- 0,
@@ -144,7 +153,8 @@ int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float 
  * the most recent init/push on this handle, and returns the device pointer of
  * that backup row, which is what "send w_t back to worker m" hands over.  If
  * the row already equals w (nothing was pushed since it was last refreshed)
- * nothing is launched.  NULL on error.
+ * nothing is launched.  NULL on error.  With DCASGD_BAK_BF16 the row holds
+ * bfloat16 values and the pointer is to be cast accordingly.
  */
 const float* dcasgd_pull(dcasgd_t h, int worker);
 
@@ -237,14 +247,15 @@ int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int st
  *   dd = snap[i]-wstar[i]; p = hdiag[i]*dd; nz = sigma*z_i; g = p+nz
  * where z_i is a standard normal drawn from Philox4x32-10 (key = seed,
  * counter = (i/4, push_idx, 0, 0), four normals per counter by Box-Muller in
- * +,-,*,/,sqrt only).  grad_out: float32[d], or bfloat16[d] (round to nearest
- * even) when as_bf16 != 0.  All pointers are device pointers, 16-byte aligned
- * (grad_out 8-byte for bfloat16).  threads/items as in dcasgd_set_launch
- * (0 = defaults).
+ * +,-,*,/,sqrt only).  formats: bit 0 set = grad_out is bfloat16[d] (round to
+ * nearest even), else float32[d]; bit 1 set = snap is bfloat16[d] (a backup
+ * row of a DCASGD_BAK_BF16 server), else float32[d].  All pointers are device
+ * pointers, 16-byte aligned (8-byte for a bfloat16 vector).  threads/items as
+ * in dcasgd_set_launch (0 = defaults).
  */
-int dcasgd_synth_grad(const float* snap, const float* hdiag, const float* wstar,
+int dcasgd_synth_grad(const void* snap, const float* hdiag, const float* wstar,
                       float sigma, uint64_t seed, uint32_t push_idx,
-                      void* grad_out, int as_bf16, size_t d, void* stream,
+                      void* grad_out, int formats, size_t d, void* stream,
                       int threads, int items);
 
 /*

@@ -18,6 +18,7 @@ MODE_C = 0
 MODE_A = 1
 GRAD_BF16 = 1 << 4
 PULL_ON_PUSH = 1 << 5
+BAK_BF16 = 1 << 6
 MAX_K = 16
 FOLD_WS_BYTES = 262656
 
@@ -101,15 +102,17 @@ def _stream_ptr(stream=None) -> int:
 def synth_grad(snap, hdiag, wstar, sigma: float, seed: int, push_idx: int, out, stream=None,
                threads: int = 0, items: int = 0) -> None:
     """Launch the synthetic worker kernel: out <- h*(snap-wstar) + sigma*z(seed, push_idx, i).
-    ``out`` is a float32 or bfloat16 CUDA tensor of snap's length."""
+    ``out`` and ``snap`` are float32 or bfloat16 CUDA tensors of the same length."""
     import torch
     d = snap.numel()
     assert hdiag.numel() == d and wstar.numel() == d and out.numel() == d
-    assert snap.dtype == hdiag.dtype == wstar.dtype == torch.float32
+    assert hdiag.dtype == wstar.dtype == torch.float32
+    assert snap.dtype in (torch.float32, torch.bfloat16)
     assert out.dtype in (torch.float32, torch.bfloat16)
+    formats = int(out.dtype == torch.bfloat16) | (int(snap.dtype == torch.bfloat16) << 1)
     rc = load().dcasgd_synth_grad(snap.data_ptr(), hdiag.data_ptr(), wstar.data_ptr(),
                                   float(sigma), int(seed), int(push_idx), out.data_ptr(),
-                                  int(out.dtype == torch.bfloat16), d, _stream_ptr(stream),
+                                  formats, d, _stream_ptr(stream),
                                   int(threads), int(items))
     _check(rc, "dcasgd_synth_grad")
 
@@ -119,19 +122,22 @@ class Server:
 
     ``w0`` is a float32 CUDA tensor holding the initial model; it becomes the
     live model ``self.w``.  ``self.bak`` is the M x stride backup matrix (row m
-    is the snapshot worker m last pulled), ``self.ms`` the MeanSquare vector.
+    is the snapshot worker m last pulled; bfloat16 with ``bak_bf16``), ``self.ms``
+    the MeanSquare vector.
     """
 
     def __init__(self, w0, M: int, eta: float, lambda0: float, mode: int,
                  ema_m: float = 0.0, eps: float = 0.0, grad_bf16: bool = False,
-                 pull_on_push: bool = False, stream=None):
+                 pull_on_push: bool = False, stream=None, bak_bf16: bool = False):
         import torch
         lib = load()
         assert w0.is_cuda and w0.dtype == torch.float32 and w0.dim() == 1 and w0.is_contiguous()
         self.d, self.M = int(w0.numel()), int(M)
         self.mode = int(mode)
         self.grad_dtype = torch.bfloat16 if grad_bf16 else torch.float32
-        flags = self.mode | (GRAD_BF16 if grad_bf16 else 0) | (PULL_ON_PUSH if pull_on_push else 0)
+        flags = self.mode | (GRAD_BF16 if grad_bf16 else 0) | (PULL_ON_PUSH if pull_on_push else 0) \
+            | (BAK_BF16 if bak_bf16 else 0)
+        self.bak_dtype = torch.bfloat16 if bak_bf16 else torch.float32
         self._h = lib.dcasgd_create(self.d, self.M, float(eta), float(lambda0), flags,
                                     float(ema_m), float(eps))
         if not self._h:
@@ -140,7 +146,7 @@ class Server:
         self.counter = None                             # device copy of t, once bound
         self.stride = (self.d + 63) // 64 * 64          # rows start 256-byte aligned
         self.w = w0
-        self.bak = torch.empty((self.M, self.stride), dtype=torch.float32, device=w0.device)
+        self.bak = torch.empty((self.M, self.stride), dtype=self.bak_dtype, device=w0.device)
         self.ms = torch.empty(self.d, dtype=torch.float32, device=w0.device) \
             if self.mode == MODE_A else None
         _check(lib.dcasgd_bind(self._h, self.w.data_ptr(), self.bak.data_ptr(), self.stride,

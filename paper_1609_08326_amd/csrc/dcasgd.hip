@@ -34,9 +34,10 @@ struct dcasgd_server {
     int M = 0;
     Hyper hp{};
     bool adaptive = false, grad_bf16 = false, pull_on_push = false;
+    bool bak_bf16 = false;            // backup rows hold bfloat16 snapshots
     float* w = nullptr;
-    float* bak = nullptr;
-    size_t bak_stride = 0;
+    void* bak = nullptr;
+    size_t bak_stride = 0;            // in elements of the backup format
     float* ms = nullptr;
     bool bound = false, ready = false;
     hipStream_t stream = nullptr;     // stream of the most recent init/push
@@ -135,13 +136,20 @@ inline int launched(dcasgd_t h) {
 }
 
 inline size_t grad_bytes(const dcasgd_server* h) { return h->d * (h->grad_bf16 ? 2 : 4); }
+inline size_t bak_elem(const dcasgd_server* h) { return h->bak_bf16 ? 2 : 4; }
+inline size_t bak_bytes(const dcasgd_server* h) {
+    return (size_t)h->M * h->bak_stride * bak_elem(h);
+}
+inline void* bak_row(const dcasgd_server* h, int worker) {
+    return static_cast<char*>(h->bak) + (size_t)worker * h->bak_stride * bak_elem(h);
+}
 
 int check_grad(dcasgd_t h, const void* grad) {
     if (!grad) return DCASGD_EINVAL;
     if (!aligned(grad, h->grad_bf16 ? 8 : 16)) return DCASGD_EALIGN;
     const size_t gb = grad_bytes(h);
     if (overlaps(grad, gb, h->w, h->d * 4) ||
-        overlaps(grad, gb, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+        overlaps(grad, gb, h->bak, bak_bytes(h)) ||
         (h->ms && overlaps(grad, gb, h->ms, h->d * 4)) ||
         (h->hp.vel && overlaps(grad, gb, h->hp.vel, h->d * 4)))
         return DCASGD_EINVAL;
@@ -150,29 +158,40 @@ int check_grad(dcasgd_t h, const void* grad) {
 
 void launch_pull(dcasgd_t h, int worker, hipStream_t s) {
     const size_t n4 = h->d / 4;
-    float* row = h->bak + (size_t)worker * h->bak_stride;
+    void* row = bak_row(h, worker);
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
     with_items(h->items, [&](auto IT) {
         with_bool(h->streaming != 0, [&](auto NT) {
-            DCASGD_LAUNCH(h, (pull_kernel<decltype(IT)::value, decltype(NT)::value>), grid,
+          with_bool(h->bak_bf16, [&](auto BB) {
+            DCASGD_LAUNCH(h, (pull_kernel<decltype(IT)::value, decltype(NT)::value,
+                                          decltype(BB)::value>), grid,
                           h->threads, s, static_cast<const float*>(h->w), row, n4, h->d);
+          });
         });
     });
 }
 
 void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipStream_t s) {
     const size_t n4 = h->d / 4;
-    float* row = h->bak + (size_t)worker * h->bak_stride;
+    void* row = bak_row(h, worker);
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
     with_bool(h->adaptive, [&](auto AD) {
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(fuse_pull, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
+            if (h->bak_bf16) {
+                // bfloat16 backups come in the fully streaming form only
+                DCASGD_LAUNCH(h, (push_kernel<decltype(AD)::value, decltype(MO)::value,
+                                              decltype(BF)::value, decltype(PL)::value,
+                                              decltype(IT)::value, 2, true>),
+                              grid, h->threads, s, h->hp, h->w, h->ms, row, grad, n4, h->d);
+                return;
+            }
             with_level(h->streaming, [&](auto NT) {
                 DCASGD_LAUNCH(h, (push_kernel<decltype(AD)::value, decltype(MO)::value,
                                               decltype(BF)::value, decltype(PL)::value,
-                                              decltype(IT)::value, decltype(NT)::value>),
+                                              decltype(IT)::value, decltype(NT)::value, false>),
                               grid, h->threads, s, h->hp, h->w, h->ms, row, grad, n4, h->d);
             });
           });
@@ -189,7 +208,7 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
     a.K = k1 - k0;
     for (int k = k0; k < k1; ++k) {
         a.grad[k - k0] = grads[k];
-        a.bak[k - k0] = h->bak + (size_t)workers[k] * h->bak_stride;
+        a.bak[k - k0] = bak_row(h, workers[k]);
     }
     const size_t n4 = h->d / 4;
     const int threads = h->batch_threads;
@@ -198,10 +217,13 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
+          with_bool(h->bak_bf16, [&](auto BB) {
             DCASGD_LAUNCH(h, (push_batch_kernel<decltype(AD)::value, decltype(MO)::value,
                                                 decltype(BF)::value, DCASGD_BATCH_KC,
-                                                decltype(NT)::value, (DCASGD_BATCH_PIPE != 0)>),
+                                                decltype(NT)::value, (DCASGD_BATCH_PIPE != 0),
+                                                decltype(BB)::value>),
                           grid, threads, s, h->hp, h->w, h->ms, a, n4, h->d);
+          });
         });
       });
      });
@@ -218,7 +240,7 @@ dcasgd_t dcasgd_create(size_t d, int M, float eta, float lambda0, int mode, floa
     const int flags = mode & ~0xF;
     if (d == 0 || M <= 0) return nullptr;
     if (variant != DCASGD_MODE_C && variant != DCASGD_MODE_A) return nullptr;
-    if (flags & ~(DCASGD_GRAD_BF16 | DCASGD_PULL_ON_PUSH)) return nullptr;
+    if (flags & ~(DCASGD_GRAD_BF16 | DCASGD_PULL_ON_PUSH | DCASGD_BAK_BF16)) return nullptr;
     if (!std::isfinite(eta) || !std::isfinite(lambda0) || !std::isfinite(ema_m) ||
         !std::isfinite(eps))
         return nullptr;
@@ -238,6 +260,7 @@ dcasgd_t dcasgd_create(size_t d, int M, float eta, float lambda0, int mode, floa
     h->adaptive = variant == DCASGD_MODE_A;
     h->grad_bf16 = (flags & DCASGD_GRAD_BF16) != 0;
     h->pull_on_push = (flags & DCASGD_PULL_ON_PUSH) != 0;
+    h->bak_bf16 = (flags & DCASGD_BAK_BF16) != 0;
     h->fresh_at.assign((size_t)M, 0);
     return h;
 }
@@ -249,13 +272,15 @@ int dcasgd_destroy(dcasgd_t h) {
     return DCASGD_OK;
 }
 
-int dcasgd_bind(dcasgd_t h, float* w, float* bak, size_t bak_stride, float* ms) {
+int dcasgd_bind(dcasgd_t h, float* w, void* bak, size_t bak_stride, float* ms) {
     if (!h) return DCASGD_EINVAL;
     if (!w || !bak || (h->adaptive && !ms)) return fail(h, DCASGD_EINVAL);
     if (bak_stride < h->d) return fail(h, DCASGD_EINVAL);
-    if (!aligned(w, 16) || !aligned(bak, 16) || (ms && !aligned(ms, 16)) || bak_stride % 4 != 0)
+    // every row must start on a 16-byte boundary: 4 floats or 8 bfloat16 values
+    if (!aligned(w, 16) || !aligned(bak, 16) || (ms && !aligned(ms, 16)) ||
+        bak_stride % (h->bak_bf16 ? 8 : 4) != 0)
         return fail(h, DCASGD_EALIGN);
-    const size_t vb = h->d * 4, bb = (size_t)h->M * bak_stride * 4;
+    const size_t vb = h->d * 4, bb = (size_t)h->M * bak_stride * bak_elem(h);
     if (overlaps(w, vb, bak, bb) || (ms && (overlaps(ms, vb, bak, bb) || overlaps(ms, vb, w, vb))))
         return fail(h, DCASGD_EINVAL);
     h->w = w;
@@ -341,7 +366,7 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
         return fail(h, DCASGD_EINVAL);
     if (h->d > ((size_t)1 << 34) || h->t > 0xFFFFFFFFull) return fail(h, DCASGD_EINVAL);
     if (!aligned(hdiag, 16) || !aligned(wstar, 16)) return fail(h, DCASGD_EALIGN);
-    const size_t vb = h->d * 4, bb = (size_t)h->M * h->bak_stride * 4;
+    const size_t vb = h->d * 4, bb = bak_bytes(h);
     const void* loss[2] = {hdiag, wstar};
     for (const void* p : loss)
         if (overlaps(p, vb, h->w, vb) || overlaps(p, vb, h->bak, bb) ||
@@ -349,7 +374,7 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
             (h->hp.vel && overlaps(p, vb, h->hp.vel, vb)))
             return fail(h, DCASGD_EINVAL);
     const size_t n4 = h->d / 4;
-    float* row = h->bak + (size_t)worker * h->bak_stride;
+    void* row = bak_row(h, worker);
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     // with a device-resident counter the kernel reads the push index itself
@@ -360,11 +385,13 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->pull_on_push, [&](auto PL) {
           with_items(h->items, [&](auto IT) {
+            with_bool(h->bak_bf16, [&](auto BB) {
               DCASGD_LAUNCH(h, (push_synth_kernel<decltype(AD)::value, decltype(MO)::value,
                                                   decltype(BF)::value, decltype(PL)::value,
-                                                  decltype(IT)::value>),
+                                                  decltype(IT)::value, decltype(BB)::value>),
                             grid, h->threads, s, h->hp, h->w, h->ms, row, hdiag, wstar, sigma, k0,
                             k1, push_idx, h->ctr, n4, h->d);
+            });
           });
         });
       });
@@ -397,7 +424,7 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
         if (!aligned(ws, 256)) return fail(h, DCASGD_EALIGN);
         const size_t wb = sizeof(FoldWorkspace);
         if (overlaps(ws, wb, h->w, h->d * 4) ||
-            overlaps(ws, wb, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+            overlaps(ws, wb, h->bak, bak_bytes(h)) ||
             (h->ms && overlaps(ws, wb, h->ms, h->d * 4)) ||
             (h->hp.vel && overlaps(ws, wb, h->hp.vel, h->d * 4)) ||
             (h->ctr && overlaps(ws, wb, h->ctr, 4)))
@@ -469,7 +496,7 @@ const float* dcasgd_pull(dcasgd_t h, int worker) {
     if (!h) return nullptr;
     if (!h->ready) { fail(h, DCASGD_ESTATE); return nullptr; }
     if (worker < 0 || worker >= h->M) { fail(h, DCASGD_EINVAL); return nullptr; }
-    const float* row = h->bak + (size_t)worker * h->bak_stride;
+    const float* row = static_cast<const float*>(bak_row(h, worker));
     if (h->fresh_at[(size_t)worker] == h->t) return row;   // already equal to w
     launch_pull(h, worker, h->stream);
     h->fresh_at[(size_t)worker] = h->t;
@@ -504,7 +531,7 @@ int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream) {
     if (!aligned(vel, 16)) return fail(h, DCASGD_EALIGN);
     const size_t vb = h->d * 4;
     if (overlaps(vel, vb, h->w, vb) ||
-        overlaps(vel, vb, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+        overlaps(vel, vb, h->bak, bak_bytes(h)) ||
         (h->ms && overlaps(vel, vb, h->ms, vb)))
         return fail(h, DCASGD_EINVAL);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -527,7 +554,7 @@ int dcasgd_bind_counter(dcasgd_t h, uint32_t* counter, void* stream) {
     if (!aligned(counter, 4)) return fail(h, DCASGD_EALIGN);
     const size_t vb = h->d * 4;
     if (overlaps(counter, 4, h->w, vb) ||
-        overlaps(counter, 4, h->bak, (size_t)h->M * h->bak_stride * 4) ||
+        overlaps(counter, 4, h->bak, bak_bytes(h)) ||
         (h->ms && overlaps(counter, 4, h->ms, vb)) ||
         (h->hp.vel && overlaps(counter, 4, h->hp.vel, vb)))
         return fail(h, DCASGD_EINVAL);
@@ -559,16 +586,18 @@ int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* 
     const size_t vb = h->d * 4, gb = grad_bytes(h);
     if (overlaps(grad_out, gb, hdiag, vb) || overlaps(grad_out, gb, wstar, vb))
         return fail(h, DCASGD_EINVAL);
-    const float* snap = h->bak + (size_t)worker * h->bak_stride;
+    const void* snap = bak_row(h, worker);
     const size_t n4 = h->d / 4;
     const unsigned grid = grid_for(n4, 256, 0);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t t_arg = h->ctr ? offset : (uint32_t)h->t + offset;
     hipStream_t s = static_cast<hipStream_t>(stream);
     with_bool(h->grad_bf16, [&](auto BF) {
-        hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, 1>), dim3(grid), dim3(256), 0, s,
-                           snap, hdiag, wstar, sigma, k0, k1, t_arg,
+      with_bool(h->bak_bf16, [&](auto BB) {
+        hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, 1, decltype(BB)::value>),
+                           dim3(grid), dim3(256), 0, s, snap, hdiag, wstar, sigma, k0, k1, t_arg,
                            static_cast<const uint32_t*>(h->ctr), grad_out, n4, h->d);
+      });
     });
     h->stream = s;
     return launched(h);
@@ -623,31 +652,36 @@ int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int st
     return DCASGD_OK;
 }
 
-int dcasgd_synth_grad(const float* snap, const float* hdiag, const float* wstar, float sigma,
-                      uint64_t seed, uint32_t push_idx, void* grad_out, int as_bf16, size_t d,
+int dcasgd_synth_grad(const void* snap, const float* hdiag, const float* wstar, float sigma,
+                      uint64_t seed, uint32_t push_idx, void* grad_out, int formats, size_t d,
                       void* stream, int threads, int items) {
+    if (formats & ~3) return DCASGD_EINVAL;
+    const bool as_bf16 = (formats & 1) != 0, snap_bf16 = (formats & 2) != 0;
     if (!snap || !hdiag || !wstar || !grad_out || d == 0) return DCASGD_EINVAL;
     if (d > ((size_t)1 << 34)) return DCASGD_EINVAL;    // the counter holds i/4 in 32 bits
     if (!std::isfinite(sigma)) return DCASGD_EINVAL;
     if (threads <= 0) threads = 256;
     if (items <= 0) items = 1;
     if (!valid_threads(threads) || !valid_items(items)) return DCASGD_EINVAL;
-    if (!aligned(snap, 16) || !aligned(hdiag, 16) || !aligned(wstar, 16) ||
+    if (!aligned(snap, snap_bf16 ? 8 : 16) || !aligned(hdiag, 16) || !aligned(wstar, 16) ||
         !aligned(grad_out, as_bf16 ? 8 : 16))
         return DCASGD_EALIGN;
     const size_t ob = d * (as_bf16 ? 2 : 4);
-    if (overlaps(grad_out, ob, snap, d * 4) || overlaps(grad_out, ob, hdiag, d * 4) ||
+    if (overlaps(grad_out, ob, snap, d * (snap_bf16 ? 2 : 4)) || overlaps(grad_out, ob, hdiag, d * 4) ||
         overlaps(grad_out, ob, wstar, d * 4))
         return DCASGD_EINVAL;
     const size_t n4 = d / 4;
     const unsigned grid = grid_for(n4, (size_t)threads * items, 0);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    with_bool(as_bf16 != 0, [&](auto BF) {
+    with_bool(as_bf16, [&](auto BF) {
         with_items(items, [&](auto IT) {
-            hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, decltype(IT)::value>),
+          with_bool(snap_bf16, [&](auto BB) {
+            hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, decltype(IT)::value,
+                                                  decltype(BB)::value>),
                                dim3(grid), dim3(threads), 0, s, snap, hdiag, wstar, sigma, k0, k1,
                                push_idx, static_cast<const uint32_t*>(nullptr), grad_out, n4, d);
+          });
         });
     });
     return hipGetLastError() == hipSuccess ? DCASGD_OK : DCASGD_EHIP;

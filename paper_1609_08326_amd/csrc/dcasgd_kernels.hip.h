@@ -82,6 +82,36 @@ __device__ __forceinline__ float load_grad1(const void* grad, size_t i) {
     else return reinterpret_cast<const float*>(grad)[i];
 }
 
+// Backup rows hold binary32 or, with BB, bfloat16 snapshots: what a pull hands
+// to the worker is round-to-nearest-even of w, and that same number is what
+// the next push of that worker is compensated against.
+template <bool BB, bool NT>
+__device__ __forceinline__ f32x4 load_bak4(const void* bak, size_t quad) {
+    return load_grad4<BB, NT>(bak, quad);
+}
+template <bool BB>
+__device__ __forceinline__ float load_bak1(const void* bak, size_t i) {
+    return load_grad1<BB>(bak, i);
+}
+template <bool BB, bool NT>
+__device__ __forceinline__ void store_bak4(void* bak, size_t quad, f32x4 v) {
+    if constexpr (BB) {
+        u16x4 r;
+        r.x = narrow_bf16(v.x); r.y = narrow_bf16(v.y);
+        r.z = narrow_bf16(v.z); r.w = narrow_bf16(v.w);
+        u16x4* p = reinterpret_cast<u16x4*>(bak) + quad;
+        if constexpr (NT) __builtin_nontemporal_store(r, p);
+        else *p = r;
+    } else {
+        store4<NT>(reinterpret_cast<float*>(bak), quad, v);
+    }
+}
+template <bool BB>
+__device__ __forceinline__ void store_bak1(void* bak, size_t i, float v) {
+    if constexpr (BB) reinterpret_cast<uint16_t*>(bak)[i] = narrow_bf16(v);
+    else reinterpret_cast<float*>(bak)[i] = v;
+}
+
 // Velocity of a float4 group.  MOM is a compile-time switch: the plain kernels
 // carry no velocity registers and no extra traffic.
 template <bool MOM>
@@ -228,9 +258,9 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
 // NT: 0 = plain accesses, 1 = gradient and backup traffic non-temporal,
 // 2 = w and MeanSquare non-temporal as well (state too large to be re-read
 // from any cache before the next push).
-template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, int NT, bool CHECKED>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, int NT, bool BB, bool CHECKED>
 __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w,
-                                          float* __restrict__ ms, float* __restrict__ bak,
+                                          float* __restrict__ ms, void* __restrict__ bak,
                                           const void* __restrict__ grad, size_t first,
                                           size_t n4) {
     f32x4 W[ITEMS], B[ITEMS], G[ITEMS], S[ITEMS], V[ITEMS];
@@ -240,7 +270,7 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
         if (!CHECKED || q < n4) {
             V[j] = load_vel4<MOM>(hp, q);
             G[j] = load_grad4<BF16, (NT >= 1)>(grad, q);
-            B[j] = load4<(NT >= 1)>(bak, q);
+            B[j] = load_bak4<BB, (NT >= 1)>(bak, q);
             W[j] = load4<(NT >= 2)>(w, q);
             if constexpr (ADAPTIVE) S[j] = load4<(NT >= 2)>(ms, q);
             else S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -256,23 +286,23 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
             store_vel4<MOM>(hp, q, V[j]);
             store4<(NT >= 2)>(w, q, W[j]);
             if constexpr (ADAPTIVE) store4<(NT >= 2)>(ms, q, S[j]);
-            if constexpr (PULL) store4<(NT >= 1)>(bak, q, W[j]);
+            if constexpr (PULL) store_bak4<BB, (NT >= 1)>(bak, q, W[j]);
         }
     }
 }
 
-template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, int NT>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, int NT, bool BB>
 __global__ void __launch_bounds__(512)
-push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __restrict__ bak,
+push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, void* __restrict__ bak,
             const void* __restrict__ grad, size_t n4, size_t d) {
     const size_t tile_quads = (size_t)blockDim.x * ITEMS;
     const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t first = tile * tile_quads + threadIdx.x;
         if ((tile + 1) * tile_quads <= n4)
-            push_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, NT, false>(hp, w, ms, bak, grad, first, n4);
+            push_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, NT, BB, false>(hp, w, ms, bak, grad, first, n4);
         else
-            push_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, NT, true>(hp, w, ms, bak, grad, first, n4);
+            push_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, NT, BB, true>(hp, w, ms, bak, grad, first, n4);
     }
     // up to three parameters beyond the last full group of four
     if (blockIdx.x == 0) {
@@ -282,10 +312,10 @@ push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __re
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
             float vi = load_vel1<MOM>(hp, i);
-            apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(grad, i), bak[i], wi, si, vi);
+            apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(grad, i), load_bak1<BB>(bak, i), wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
-            if constexpr (PULL) bak[i] = wi;
+            if constexpr (PULL) store_bak1<BB>(bak, i, wi);
             store_vel1<MOM>(hp, i, vi);
         }
     }
@@ -294,7 +324,7 @@ push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, float* __re
 // ---- K queued pushes in one pass (push; pull; push; pull; ...) -------------------
 struct BatchArgs {
     const void* grad[16];   // grad[k]: gradient of queue entry k
-    float* bak[16];         // bak[k]: backup row of the worker of entry k (all distinct)
+    void* bak[16];          // bak[k]: backup row of the worker of entry k (all distinct)
     int K;
 };
 
@@ -305,17 +335,17 @@ struct BatchArgs {
 // the current one, so the sqrt/divide work of one group hides the memory
 // latency of the next (the rows of a queue are distinct, so those loads do
 // not depend on the stores they overtake).
-template <bool BF16, int KC, bool NT>
+template <bool BF16, int KC, bool NT, bool BB>
 __device__ __forceinline__ void batch_load(const BatchArgs& a, int k0, size_t q,
                                            f32x4 (&G)[KC], f32x4 (&B)[KC]) {
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
         G[kk] = load_grad4<BF16, NT>(a.grad[k0 + kk], q);
-        B[kk] = load4<NT>(a.bak[k0 + kk], q);
+        B[kk] = load_bak4<BB, NT>(a.bak[k0 + kk], q);
     }
 }
 
-template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool PIPE, bool CHECKED>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool PIPE, bool BB, bool CHECKED>
 __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ w,
                                            float* __restrict__ ms, const BatchArgs& a,
                                            size_t q, size_t n4) {
@@ -328,14 +358,14 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
     f32x4 G[KC], B[KC];
     if constexpr (PIPE) {
         f32x4 Gn[KC], Bn[KC];
-        if (full > 0) batch_load<BF16, KC, NT>(a, 0, q, G, B);
+        if (full > 0) batch_load<BF16, KC, NT, BB>(a, 0, q, G, B);
         for (int k0 = 0; k0 < full; k0 += KC) {
             const bool more = k0 + KC < full;
-            if (more) batch_load<BF16, KC, NT>(a, k0 + KC, q, Gn, Bn);
+            if (more) batch_load<BF16, KC, NT, BB>(a, k0 + KC, q, Gn, Bn);
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
                 apply_push4<ADAPTIVE, MOM>(hp, G[kk], B[kk], W, S, V);
-                store4<NT>(a.bak[k0 + kk], q, W);
+                store_bak4<BB, NT>(a.bak[k0 + kk], q, W);
             }
             if (more) {
 #pragma unroll
@@ -344,26 +374,26 @@ __device__ __forceinline__ void batch_quad(const Hyper& hp, float* __restrict__ 
         }
     } else {
         for (int k0 = 0; k0 < full; k0 += KC) {
-            batch_load<BF16, KC, NT>(a, k0, q, G, B);
+            batch_load<BF16, KC, NT, BB>(a, k0, q, G, B);
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
                 apply_push4<ADAPTIVE, MOM>(hp, G[kk], B[kk], W, S, V);
-                store4<NT>(a.bak[k0 + kk], q, W);
+                store_bak4<BB, NT>(a.bak[k0 + kk], q, W);
             }
         }
     }
     for (int k = full; k < a.K; ++k) {
         const f32x4 g = load_grad4<BF16, NT>(a.grad[k], q);
-        const f32x4 b = load4<NT>(a.bak[k], q);
+        const f32x4 b = load_bak4<BB, NT>(a.bak[k], q);
         apply_push4<ADAPTIVE, MOM>(hp, g, b, W, S, V);
-        store4<NT>(a.bak[k], q, W);
+        store_bak4<BB, NT>(a.bak[k], q, W);
     }
     store4<false>(w, q, W);
     if constexpr (ADAPTIVE) store4<false>(ms, q, S);
     store_vel4<MOM>(hp, q, V);
 }
 
-template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool PIPE>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool PIPE, bool BB>
 __global__ void __launch_bounds__(256)
 push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, BatchArgs a,
                   size_t n4, size_t d) {
@@ -371,9 +401,9 @@ push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, Batch
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t q = tile * blockDim.x + threadIdx.x;
         if ((tile + 1) * blockDim.x <= n4)
-            batch_quad<ADAPTIVE, MOM, BF16, KC, NT, PIPE, false>(hp, w, ms, a, q, n4);
+            batch_quad<ADAPTIVE, MOM, BF16, KC, NT, PIPE, BB, false>(hp, w, ms, a, q, n4);
         else
-            batch_quad<ADAPTIVE, MOM, BF16, KC, NT, PIPE, true>(hp, w, ms, a, q, n4);
+            batch_quad<ADAPTIVE, MOM, BF16, KC, NT, PIPE, BB, true>(hp, w, ms, a, q, n4);
     }
     if (blockIdx.x == 0) {
         const size_t i = 4 * n4 + threadIdx.x;
@@ -383,8 +413,9 @@ push_batch_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, Batch
             if constexpr (ADAPTIVE) si = ms[i];
             float vi = load_vel1<MOM>(hp, i);
             for (int k = 0; k < a.K; ++k) {
-                apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(a.grad[k], i), a.bak[k][i], wi, si, vi);
-                a.bak[k][i] = wi;
+                apply_push<ADAPTIVE, MOM>(hp, load_grad1<BF16>(a.grad[k], i),
+                                          load_bak1<BB>(a.bak[k], i), wi, si, vi);
+                store_bak1<BB>(a.bak[k], i, wi);
             }
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
@@ -577,9 +608,9 @@ fold_order_kernel(FoldArgs a, FoldWorkspace* __restrict__ ws, int nblocks) {
 }
 
 // ---- pull: w_bak(m) <- w ---------------------------------------------------------
-template <int ITEMS, bool NT>
+template <int ITEMS, bool NT, bool BB>
 __global__ void __launch_bounds__(512)
-pull_kernel(const float* __restrict__ w, float* __restrict__ bak, size_t n4, size_t d) {
+pull_kernel(const float* __restrict__ w, void* __restrict__ bak, size_t n4, size_t d) {
     const size_t tile_quads = (size_t)blockDim.x * ITEMS;
     const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
@@ -593,12 +624,12 @@ pull_kernel(const float* __restrict__ w, float* __restrict__ bak, size_t n4, siz
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             const size_t q = first + (size_t)j * blockDim.x;
-            if (q < n4) store4<NT>(bak, q, V[j]);
+            if (q < n4) store_bak4<BB, NT>(bak, q, V[j]);
         }
     }
     if (blockIdx.x == 0) {
         const size_t i = 4 * n4 + threadIdx.x;
-        if (i < d) bak[i] = w[i];
+        if (i < d) store_bak1<BB>(bak, i, w[i]);
     }
 }
 
@@ -739,9 +770,9 @@ __global__ void counter_add_kernel(uint32_t* ctr, uint32_t n) {
 }
 
 // g = h * (snap - wstar) + sigma * z, four parameters per Philox counter.
-template <bool BF16, int ITEMS>
+template <bool BF16, int ITEMS, bool BB>
 __global__ void __launch_bounds__(512)
-synth_grad_kernel(const float* __restrict__ snap, const float* __restrict__ hdiag,
+synth_grad_kernel(const void* __restrict__ snap, const float* __restrict__ hdiag,
                   const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
                   uint32_t t_arg, const uint32_t* __restrict__ ctr, void* __restrict__ out,
                   size_t n4, size_t d) {
@@ -757,7 +788,7 @@ synth_grad_kernel(const float* __restrict__ snap, const float* __restrict__ hdia
             if (q < n4) {
                 // the snapshot is read again by the push that follows: leave it
                 // cacheable; the loss vectors stream through once per arrival
-                A[j] = load4<false>(snap, q);
+                A[j] = load_bak4<BB, false>(snap, q);
                 H[j] = load4<true>(hdiag, q);
                 O[j] = load4<true>(wstar, q);
             } else {
@@ -790,7 +821,7 @@ synth_grad_kernel(const float* __restrict__ snap, const float* __restrict__ hdia
         const f32x4 z = normals_for_quad(k0, k1, t, (uint32_t)n4);
         const float zz[4] = {z.x, z.y, z.z, z.w};
         for (size_t i = 4 * n4; i < d; ++i) {
-            const float g = synth_one(snap[i], hdiag[i], wstar[i], sigma, zz[i - 4 * n4]);
+            const float g = synth_one(load_bak1<BB>(snap, i), hdiag[i], wstar[i], sigma, zz[i - 4 * n4]);
             if constexpr (BF16) reinterpret_cast<uint16_t*>(out)[i] = narrow_bf16(g);
             else reinterpret_cast<float*>(out)[i] = g;
         }
@@ -812,9 +843,9 @@ __device__ __forceinline__ float synth_delivered(float snap, float h, float wsta
     else return g;
 }
 
-template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, bool CHECKED>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, bool BB, bool CHECKED>
 __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restrict__ w,
-                                                float* __restrict__ ms, float* __restrict__ bak,
+                                                float* __restrict__ ms, void* __restrict__ bak,
                                                 const float* __restrict__ hdiag,
                                                 const float* __restrict__ wstar, float sigma,
                                                 uint32_t k0, uint32_t k1, uint32_t t,
@@ -825,7 +856,7 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
         const size_t q = first + (size_t)j * blockDim.x;
         if (!CHECKED || q < n4) {
             V[j] = load_vel4<MOM>(hp, q);
-            B[j] = load4<true>(bak, q);
+            B[j] = load_bak4<BB, true>(bak, q);
             H[j] = load4<true>(hdiag, q);
             O[j] = load4<true>(wstar, q);
             W[j] = load4<true>(w, q);
@@ -848,15 +879,15 @@ __device__ __forceinline__ void push_synth_tile(const Hyper& hp, float* __restri
             store_vel4<MOM>(hp, q, V[j]);
             store4<true>(w, q, W[j]);
             if constexpr (ADAPTIVE) store4<true>(ms, q, S[j]);
-            if constexpr (PULL) store4<true>(bak, q, W[j]);
+            if constexpr (PULL) store_bak4<BB, true>(bak, q, W[j]);
         }
     }
 }
 
-template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS>
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, bool BB>
 __global__ void __launch_bounds__(512)
 push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
-                  float* __restrict__ bak, const float* __restrict__ hdiag,
+                  void* __restrict__ bak, const float* __restrict__ hdiag,
                   const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
                   uint32_t t_arg, const uint32_t* __restrict__ ctr, size_t n4, size_t d) {
     const uint32_t t = push_index(t_arg, ctr);
@@ -865,16 +896,16 @@ push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t first = tile * tile_quads + threadIdx.x;
         if ((tile + 1) * tile_quads <= n4)
-            push_synth_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, false>(hp, w, ms, bak, hdiag, wstar, sigma,
-                                                                k0, k1, t, first, n4);
+            push_synth_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, BB, false>(
+                hp, w, ms, bak, hdiag, wstar, sigma, k0, k1, t, first, n4);
         else
-            push_synth_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, true>(hp, w, ms, bak, hdiag, wstar, sigma,
-                                                               k0, k1, t, first, n4);
+            push_synth_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, BB, true>(
+                hp, w, ms, bak, hdiag, wstar, sigma, k0, k1, t, first, n4);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0 && 4 * n4 < d) {
         const f32x4 z = normals_for_quad(k0, k1, t, (uint32_t)n4);
         for (size_t i = 4 * n4; i < d; ++i) {
-            const float b = bak[i];
+            const float b = load_bak1<BB>(bak, i);
             const float g = synth_delivered<BF16>(b, hdiag[i], wstar[i], sigma, z[i - 4 * n4]);
             float wi = w[i];
             float si = 0.f;
@@ -883,7 +914,7 @@ push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
             apply_push<ADAPTIVE, MOM>(hp, g, b, wi, si, vi);
             w[i] = wi;
             if constexpr (ADAPTIVE) ms[i] = si;
-            if constexpr (PULL) bak[i] = wi;
+            if constexpr (PULL) store_bak1<BB>(bak, i, wi);
             store_vel1<MOM>(hp, i, vi);
         }
     }

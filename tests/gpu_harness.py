@@ -28,7 +28,7 @@ class DeviceRun:
 
     def __init__(self, wl: W.Workload, *, fused: bool = True, batched: bool = False,
                  launch: dict | None = None, synth_launch: tuple = (0, 0), momentum: float = 0.0,
-                 hdiag=None, wstar=None, arrivals=None):
+                 hdiag=None, wstar=None, arrivals=None, bak_bf16: bool = False):
         import torch
         from paper_1609_08326_amd import binding as B
         dev = torch.device("cuda:0")
@@ -40,7 +40,8 @@ class DeviceRun:
         ws = torch.from_numpy(self.wstar_host).to(dev)
         w = torch.from_numpy(wl.w0()).to(dev)
         sv = B.Server(w, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps,
-                      grad_bf16=wl.grad_bf16, pull_on_push=fused and not batched)
+                      grad_bf16=wl.grad_bf16, pull_on_push=fused and not batched,
+                      bak_bf16=bak_bf16)
         if launch:
             sv.set_launch(**launch)
         if momentum:
@@ -81,12 +82,12 @@ class DeviceRun:
         self.server = sv
         self.w = sv.w.cpu().numpy()
         self.ms = sv.ms.cpu().numpy() if sv.ms is not None else None
-        self.bak = sv.bak[:, : wl.d].cpu().numpy()
+        self.bak = sv.bak[:, : wl.d].float().cpu().numpy()
         self.vel = sv.vel.cpu().numpy() if getattr(sv, "vel", None) is not None else None
 
 
 def oracle_run(wl: W.Workload, hdiag, wstar, arrivals, idx=None, nthreads: int = 8,
-               momentum: float = 0.0):
+               momentum: float = 0.0, bak_bf16: bool = False):
     """The oracle on the same inputs; idx selects a subset of elements."""
     w0 = wl.w0()
     if idx is not None:
@@ -94,6 +95,8 @@ def oracle_run(wl: W.Workload, hdiag, wstar, arrivals, idx=None, nthreads: int =
     sv = oracle.Server(w0, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
     if momentum:
         sv.set_momentum(momentum)
+    if bak_bf16:
+        sv.set_backup_bf16()
     sv.run(arrivals, hdiag, wstar, wl.sigma, wl.seed, gidx=idx, as_bf16=wl.grad_bf16,
            nthreads=nthreads)
     return sv
