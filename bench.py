@@ -31,19 +31,20 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 VALU_PEAK_TLANE = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
-def algorithmic_bytes_per_update(wl, unfused: bool = False) -> float:
+def algorithmic_bytes_per_update(wl, unfused: bool = False, bak_bf16: bool = False) -> float:
     """Bytes the method itself must move per element per applied push
     (fused push+pull): reads w, backup, gradient (+MeanSquare), writes w,
     backup (+MeanSquare).  Queue of K: w/MeanSquare once per queue."""
     g = 2 if wl.grad_bf16 else 4
+    b = 2 if bak_bf16 else 4        # backup element, read once and written once per push
     adaptive = wl.mode == 1
     if wl.order == "sync":      # fold: w (+MeanSquare) once, K gradients, no backups
         return ((16 if adaptive else 8) + wl.K * g) / wl.K
     if wl.K > 1:
-        per_queue = (16 if adaptive else 8) + wl.K * (g + 4 + 4)
+        per_queue = (16 if adaptive else 8) + wl.K * (g + b + b)
         return per_queue / wl.K
     # unfused: the separate pull reads w once more
-    return (4 + 4 + g + 4 + 4) + (8 if adaptive else 0) + (4 if unfused else 0)
+    return (4 + b + g + 4 + b) + (8 if adaptive else 0) + (4 if unfused else 0)
 
 
 def read_profile(name: str, key: str = "traffic_bytes_per_launch"):
@@ -57,7 +58,7 @@ def read_profile(name: str, key: str = "traffic_bytes_per_launch"):
         return None
 
 
-def cpu_baseline(wl, target_s: float):
+def cpu_baseline(wl, target_s: float, bak_bf16: bool = False):
     """Time the oracle (as it stands) on a bounded sample of the workload:
     a leading slice of the parameter vector, the workload's arrival order
     (continued with the same generator if the sample needs more arrivals)."""
@@ -72,6 +73,8 @@ def cpu_baseline(wl, target_s: float):
         order = wl.replace(T=-(-T // wl.K) * wl.K).arrivals()[:T]
         sv = oracle.Server(np.zeros(n, dtype=np.float32), wl.M, wl.eta, wl.lambda0, wl.mode,
                            wl.ema_m, wl.eps)
+        if bak_bf16:
+            sv.set_backup_bf16()
         t0 = time.perf_counter()
         sv.run(order, hd, ws, wl.sigma, wl.seed, as_bf16=wl.grad_bf16, nthreads=threads)
         return time.perf_counter() - t0
@@ -121,6 +124,9 @@ def main() -> int:
     ap.add_argument("--stream-events", action="store_true",
                     help="additionally record stream events between the kernels of a step and "
                          "report their intervals (adds a dispatch gap per event)")
+    ap.add_argument("--bak-bf16", action="store_true",
+                    help="snapshots handed out and kept as bfloat16 (a storage variant; the "
+                         "default measures the float32 backups of the configurations)")
     ap.add_argument("--ordered", action="store_true",
                     help="fold workload: after the timed region, time the same steps again "
                          "with the gradients ranked by norm on the device before each fold")
@@ -153,7 +159,8 @@ def main() -> int:
     ws = torch.from_numpy(wl.wstar()).to(dev)
     w = torch.from_numpy(wl.w0()).to(dev)
     sv = B.Server(w, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps,
-                  grad_bf16=wl.grad_bf16, pull_on_push=not batched and not args.unfused)
+                  grad_bf16=wl.grad_bf16, pull_on_push=not batched and not args.unfused,
+                  bak_bf16=args.bak_bf16)
     if args.threads or args.items or args.max_blocks or args.streaming >= 0:
         sv.set_launch(args.threads, args.items, args.max_blocks,
                       args.streaming if args.streaming >= 0 else 2)
@@ -221,9 +228,11 @@ def main() -> int:
     updates = wl.d * K * n_steps
     value = updates / elapsed
     unfused = args.unfused and K == 1 and not sync
-    bpu = algorithmic_bytes_per_update(wl, unfused)
+    bpu = algorithmic_bytes_per_update(wl, unfused, args.bak_bf16)
     kname = ("sync_fold_J%d" % K if sync else "push_batch_K%d" % K if batched
              else "push_then_pull" if unfused else "push_fused")
+    if args.bak_bf16 and not sync:
+        kname += "_bak16"
     out = {
         "metric": "element-updates/sec",
         "value": value,
@@ -239,6 +248,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "M": wl.M, "K": K,
                    "variant": "DC-ASGD-a" if wl.mode == 1 else "DC-ASGD-c",
+                   "snapshots": "bf16" if args.bak_bf16 else "f32",
                    "step": ("synth_grad x%d + synchronous fold" if sync else
                             "synth_grad x%d + fused push+pull") % K},
     }
@@ -276,7 +286,7 @@ def main() -> int:
         out["worker_and_gaps_ms_per_step"] = 1e3 * elapsed / n_steps - push_ms
         if stream_events:
             synth_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / n_steps
-            synth_bytes = (12 + (2 if wl.grad_bf16 else 4)) * wl.d * K
+            synth_bytes = (8 + (2 if args.bak_bf16 else 4) + (2 if wl.grad_bf16 else 4)) * wl.d * K
             out["stream_event_intervals"] = {
                 "worker_ms_per_step": synth_ms,
                 "server_ms_per_step": sum(e[1].elapsed_time(e[2]) for e in ev) / n_steps,
@@ -292,7 +302,7 @@ def main() -> int:
             sv.push_synth(int(arrivals[n_warm + i]), hd, ws, wl.sigma, wl.seed)
         torch.cuda.synchronize()
         fe = time.perf_counter() - t0
-        fbytes = (32 + (0 if wl.mode == 1 else -8)) * wl.d
+        fbytes = (32 + (0 if wl.mode == 1 else -8) - (4 if args.bak_bf16 else 0)) * wl.d
         out["fused_worker_path"] = {"value": wl.d * n_steps / fe, "unit": "element-updates/s",
                                     "ms_per_step": 1e3 * fe / n_steps,
                                     "algorithmic_GBs": fbytes * n_steps / fe / 1e9,
@@ -371,7 +381,7 @@ def main() -> int:
                                              else "worker gradient + fused push+pull per arrival, ")
                                             + "launches replayed from one HIP graph"}
     if args.cpu_seconds > 0 and not sync:
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds, args.bak_bf16)
     print(json.dumps(out), flush=True)
     return 0
 

@@ -17,6 +17,9 @@ def test_algorithmic_bytes_per_update():
     assert bench.algorithmic_bytes_per_update(c[3]) == 13      # (16 + 16*12) / 16
     assert bench.algorithmic_bytes_per_update(c[4]) == 26      # bf16 gradient
     assert bench.algorithmic_bytes_per_update(W.get("fold")) == 5
+    assert bench.algorithmic_bytes_per_update(c[2], bak_bf16=True) == 24   # backup 2 B in, 2 B out
+    assert bench.algorithmic_bytes_per_update(c[4], bak_bf16=True) == 22
+    assert bench.algorithmic_bytes_per_update(c[3], bak_bf16=True) == 9    # (16 + 16*8) / 16
 
 
 def test_more_than_one_gpu_is_refused():
