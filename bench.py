@@ -210,20 +210,25 @@ def main() -> int:
             step(n_warm + i, ev[i] if stream_events else None)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t_start
+        each = None
         try:
-            ms, launches = sv.timing_read() if kernel_events else (0.0, 0)
+            if kernel_events:
+                each = sv.timing_read_each()
+                ms, launches = float(each.sum(dtype="float64")), int(each.size)
+            else:
+                ms, launches = 0.0, 0
         except B.DcasgdError:
             ms, launches = 0.0, 0
         sv.timing(False)
-        return dt, ms, launches
+        return dt, ms, launches, each
 
-    elapsed, kernel_ms, kernel_launches = timed_region()
+    elapsed, kernel_ms, kernel_launches, kernel_each = timed_region()
     if kernel_events and (kernel_launches == 0 or not kernel_ms > 0.0):
         # the runtime gave no times for launch-attached events: measure again
         # with stream events around the kernels instead
         kernel_events, stream_events = False, True
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_steps)]
-        elapsed, kernel_ms, kernel_launches = timed_region()
+        elapsed, kernel_ms, kernel_launches, kernel_each = timed_region()
 
     updates = wl.d * K * n_steps
     value = updates / elapsed
@@ -280,6 +285,13 @@ def main() -> int:
                                "bytes_per_element_update": bpu}
         out["server_update_only"] = {"value": wl.d * K / (push_ms * 1e-3),
                                      "unit": "element-updates/s"}
+        if kernel_events and kernel_each is not None and kernel_each.size >= n_steps \
+                and kernel_each.size % n_steps == 0:
+            # spread over the region: server-kernel time of each step (its launches added up)
+            import numpy as np
+            per_step = kernel_each.reshape(n_steps, -1).sum(axis=1, dtype="float64")
+            p10, p50, p90 = (float(x) for x in np.percentile(per_step, [10, 50, 90]))
+            out["roofline"]["launch_ms_p10_median_p90"] = [p10, p50, p90]
         out["roofline"]["launches_timed"] = kernel_launches
         out["roofline"]["timed_by"] = ("HIP events attached to each launch" if kernel_events
                                        else "HIP stream events around each launch")

@@ -222,6 +222,10 @@ int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* 
  */
 int dcasgd_timing(dcasgd_t h, int enable);
 int dcasgd_timing_read(dcasgd_t h, double* total_ms, uint64_t* launches);
+/* The same read, launch by launch: each_ms[i] (host array of `capacity` floats)
+ * receives the duration of the i-th timed launch since the last read, in launch
+ * order, for i < min(*launches, capacity). */
+int dcasgd_timing_read_each(dcasgd_t h, float* each_ms, size_t capacity, uint64_t* launches);
 
 /*
  * Change the learning rate for all later pushes (the experiments of Section 6

@@ -51,6 +51,8 @@ _PROTOTYPES = {
                                      C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "dcasgd_timing": (C.c_int, [C.c_void_p, C.c_int]),
     "dcasgd_timing_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
+    "dcasgd_timing_read_each": (C.c_int, [C.c_void_p, C.POINTER(C.c_float), C.c_size_t,
+                                          C.POINTER(C.c_uint64)]),
     "dcasgd_set_eta": (C.c_int, [C.c_void_p, C.c_float]),
     "dcasgd_set_launch": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]),
     "dcasgd_synth_grad": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_uint64,
@@ -211,6 +213,16 @@ class Server:
         ms, n = C.c_double(0.0), C.c_uint64(0)
         _check(load().dcasgd_timing_read(self._h, C.byref(ms), C.byref(n)), "dcasgd_timing_read")
         return float(ms.value), int(n.value)
+
+    def timing_read_each(self, capacity: int = 65536):
+        """Durations in milliseconds of the timed launches since the last read, in
+        launch order (numpy float32 array); waits for them."""
+        import numpy as np
+        buf = np.zeros(int(capacity), dtype=np.float32)
+        n = C.c_uint64(0)
+        _check(load().dcasgd_timing_read_each(self._h, buf.ctypes.data_as(C.POINTER(C.c_float)),
+                                              buf.size, C.byref(n)), "dcasgd_timing_read_each")
+        return buf[: min(int(n.value), buf.size)].copy()
 
     def set_eta(self, eta: float) -> None:
         """Learning rate of all later pushes (step schedules)."""

@@ -630,6 +630,23 @@ int dcasgd_timing_read(dcasgd_t h, double* total_ms, uint64_t* launches) {
     return DCASGD_OK;
 }
 
+int dcasgd_timing_read_each(dcasgd_t h, float* each_ms, size_t capacity, uint64_t* launches) {
+    if (!h) return DCASGD_EINVAL;
+    if (!launches || (capacity > 0 && !each_ms)) return fail(h, DCASGD_EINVAL);
+    const size_t n = h->timing_used / 2;
+    for (size_t i = 0; i < n; ++i) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(h->timing_events[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, h->timing_events[2 * i], h->timing_events[2 * i + 1]) !=
+                hipSuccess)
+            return fail(h, DCASGD_EHIP);
+        if (i < capacity) each_ms[i] = ms;
+    }
+    *launches = n;
+    h->timing_used = 0;
+    return DCASGD_OK;
+}
+
 int dcasgd_set_eta(dcasgd_t h, float eta) {
     if (!h) return DCASGD_EINVAL;
     if (!std::isfinite(eta)) return fail(h, DCASGD_EINVAL);

@@ -343,3 +343,10 @@ def test_per_launch_timing_counts_launches_and_changes_nothing():
         sv2.push(int(m), g)
     torch.cuda.synchronize()
     assert_same_bits(sv2.w.cpu().numpy(), timed.w, "timed launches give the same w")
+    each = sv2.timing_read_each()                # launch by launch, in order
+    assert each.size == len(timed.arrivals) and np.all(each > 0.0) and float(each.sum()) < 1000.0
+    assert sv2.timing_read_each().size == 0
+    sv2.push(0, g)
+    sv2.push(1, g)
+    assert sv2.timing_read_each(capacity=1).size == 1     # a short buffer still ends the interval
+    assert sv2.timing_read() == (0.0, 0)
