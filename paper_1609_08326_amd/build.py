@@ -56,6 +56,29 @@ def build_probe(force: bool = True, verbose: bool = False) -> str:
     return PROBE
 
 
+CHECKER_SRC = os.path.join(CSRC, "lambda_check.hip")
+CHECKER = os.path.join(_PKG, "lambda_check")
+
+
+def build_checker(force: bool = True, verbose: bool = False) -> str:
+    """Build the stand-alone checker of the short sqrt/divide forms (an executable that
+    includes the kernels' header, so it tests the very functions the library runs)."""
+    deps = [CHECKER_SRC, os.path.join(CSRC, "dcasgd_kernels.hip.h")]
+    stale = (not os.path.exists(CHECKER)) or \
+        any(os.path.getmtime(CHECKER) < os.path.getmtime(p) for p in deps)
+    if force or stale:
+        tmp = CHECKER + ".tmp.%d" % os.getpid()
+        cmd = [HIPCC, "--offload-arch=gfx950", "-std=c++17", "-O3", "-ffp-contract=off",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", CSRC,
+               CHECKER_SRC, "-o", tmp]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        os.replace(tmp, CHECKER)
+    return CHECKER
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))
     print(build_probe(force=True, verbose=True))
+    print(build_checker(force=True, verbose=True))

@@ -25,6 +25,9 @@ using namespace dcasgd;
 // Launches that can be timed between two dcasgd_timing_read calls; further
 // ones run untimed, so an unread handle does not pile up events.
 #define DCASGD_MAX_TIMED 65536
+#ifndef DCASGD_FOLD_KC
+#define DCASGD_FOLD_KC 4      // gradients of a fold a lane loads before it starts on them
+#endif
 #ifndef DCASGD_NORM_ITEMS
 #define DCASGD_NORM_ITEMS 4   // float4 groups a lane of the norm kernel has in flight
 #endif
@@ -467,8 +470,8 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
         with_bool(h->streaming != 0, [&](auto NT) {
           with_bool(ordered, [&](auto OR) {
             DCASGD_LAUNCH(h, (sync_fold_kernel<decltype(AD)::value, decltype(MO)::value,
-                                               decltype(BF)::value, 4, decltype(NT)::value,
-                                               decltype(OR)::value>),
+                                               decltype(BF)::value, DCASGD_FOLD_KC,
+                                               decltype(NT)::value, decltype(OR)::value>),
                           grid, threads, s, hp, h->w, h->ms, a,
                           static_cast<const FoldWorkspace*>(ws), n4, h->d);
           });

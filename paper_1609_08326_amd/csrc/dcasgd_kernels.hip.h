@@ -169,37 +169,45 @@ __device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
     take_step<MOM>(hp, gdc, w, v);
 }
 
-// Correctly rounded square root and quotient without the exponent rescaling and
-// special-value fix-ups of the general expansions.  While operands and results
-// stay far from both ends of the exponent range the rescaling is the identity,
-// so these give the same bits with about a third fewer instructions: hardware
-// estimate (within one ulp), then the neighbour whose residual has the right
-// sign (sqrt) or two residual corrections of the quotient (divide).
-__device__ __forceinline__ float sqrt_rn_midrange(float x) {
+// lambda0 / sqrt(x) as two correctly rounded operations, without the exponent
+// rescaling and special-value fix-ups of the general expansions.  While
+// operands and results stay far from both ends of the exponent range the
+// rescaling is the identity, so these give the same bits in ten instructions
+// instead of about thirty.
+// Root: hardware estimate s (within one ulp), its exact residual x - s*s, and
+// one Newton step with h = 1/(2s) taken from the hardware reciprocal of s.
+// Quotient: that same reciprocal y (of s, hence within two ulps of 1/root) is
+// sharpened by one Newton step and seeds a*y; one residual correction follows.
+// (With the unsharpened y and two corrections about two quotients in a
+// billion come out one ulp off.)
+// Both are checked against the IEEE operations by the stand-alone checker next
+// to this file: every admitted radicand for the root; every pair of root and
+// numerator significands, 1.4e14 cases, for the quotient; no mismatch.
+__device__ __forceinline__ float root_rn_midrange(float x, float& y) {
     const float s = __builtin_amdgcn_sqrtf(x);
-    const float s_dn = __uint_as_float(__float_as_uint(s) - 1u);
-    const float s_up = __uint_as_float(__float_as_uint(s) + 1u);
-    const float r_dn = __builtin_fmaf(-s_dn, s, x);
-    const float r_up = __builtin_fmaf(-s_up, s, x);
-    float r = (r_dn <= 0.0f) ? s_dn : s;
-    r = (r_up > 0.0f) ? s_up : r;
-    return r;
+    y = __builtin_amdgcn_rcpf(s);
+    const float r = __builtin_fmaf(-s, s, x);
+    const float h = 0.5f * y;
+    return __builtin_fmaf(r, h, s);
 }
 
-__device__ __forceinline__ float div_rn_midrange(float a, float b) {
-    float y = __builtin_amdgcn_rcpf(b);
+// a / b for b = root_rn_midrange(x, y)
+__device__ __forceinline__ float quotient_rn_midrange(float a, float b, float y) {
     const float e = __builtin_fmaf(-b, y, 1.0f);
     y = __builtin_fmaf(e, y, y);
-    float q = a * y;
-    float r = __builtin_fmaf(-b, q, a);
-    q = __builtin_fmaf(r, y, q);
-    r = __builtin_fmaf(-b, q, a);
+    const float q = a * y;
+    const float r = __builtin_fmaf(-b, q, a);
     return __builtin_fmaf(r, y, q);
 }
 
-// 2^-64 <= x < 2^64 (false for zero, denormals, negatives, inf, NaN)
+// Radicands the short forms are used for: 2^-64 <= x < 2^64 (so not zero,
+// denormal, negative, inf or NaN), except an all-ones significand with an even
+// exponent field.  There sqrt(x) lies 2^-50 (relative) below the midpoint of
+// two neighbours and the Newton step lands exactly on it; that one pattern per
+// pair of binades takes the general expansion instead.
 __device__ __forceinline__ bool in_midrange(float x) {
-    return (__float_as_uint(x) - 0x1F800000u) < 0x40000000u;
+    const uint32_t u = __float_as_uint(x);
+    return (u - 0x1F800000u) < 0x40000000u && (u & 0x00FFFFFFu) != 0x007FFFFFu;
 }
 
 // Four parameters at once.  The adaptive lambda needs sqrt and a divide per
@@ -231,8 +239,11 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
         }
         if (__builtin_amdgcn_ballot_w64(!mid) == 0) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                lam[c] = div_rn_midrange(hp.lambda0, sqrt_rn_midrange(under[c]));
+            for (int c = 0; c < 4; ++c) {
+                float y;
+                const float root = root_rn_midrange(under[c], y);
+                lam[c] = quotient_rn_midrange(hp.lambda0, root, y);
+            }
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c) lam[c] = hp.lambda0 / __builtin_sqrtf(under[c]);

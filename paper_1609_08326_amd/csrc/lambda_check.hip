@@ -1,0 +1,156 @@
+// Stand-alone checker for the short forms of sqrt and divide used by the
+// adaptive-lambda kernels (root_rn_midrange / quotient_rn_midrange): compares
+// them with the IEEE operations (correctly rounded sqrt and division as the
+// compiler expands them) over their whole domain.
+//
+//   lambda_check roots                 every radicand in [2^-64, 2^64)
+//   lambda_check quotients FIRST COUNT every radicand of two binades ([1, 4):
+//                                      all significands, both exponent parities)
+//                                      against numerators 1 + k*2^-23 for
+//                                      k = FIRST .. FIRST+COUNT-1  (COUNT <= 2^23)
+//   lambda_check sampled N SEED        N random (radicand, numerator) pairs over
+//                                      the whole admitted range, both signs
+// Prints the number of cases and of mismatches, the first few mismatches, and
+// exits non-zero if there is any.
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "dcasgd_kernels.hip.h"
+
+using namespace dcasgd;
+
+#define CHECK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { \
+    std::fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_)); std::exit(2); } } while (0)
+
+struct Report {
+    unsigned long long mismatches;
+    unsigned long long skipped;   // radicands the kernels do not take the short path for
+    uint32_t first[8][4];   // radicand bits, numerator bits, got, expected
+};
+
+__device__ void note(Report* rep, uint32_t x, uint32_t a, float got, float want) {
+    const unsigned long long slot = atomicAdd(&rep->mismatches, 1ull);
+    if (slot < 8) {
+        rep->first[slot][0] = x;
+        rep->first[slot][1] = a;
+        rep->first[slot][2] = __float_as_uint(got);
+        rep->first[slot][3] = __float_as_uint(want);
+    }
+}
+
+// radicand bits first .. first+count-1
+__global__ void check_roots(uint32_t first, uint32_t count, Report* rep) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += gridDim.x * blockDim.x) {
+        const float x = __uint_as_float(first + i);
+        if (!in_midrange(x)) { atomicAdd(&rep->skipped, 1ull); continue; }
+        float y;
+        const float got = root_rn_midrange(x, y);
+        const float want = __builtin_sqrtf(x);
+        if (__float_as_uint(got) != __float_as_uint(want)) note(rep, first + i, 0u, got, want);
+    }
+}
+
+// thread <-> radicand in [1, 4); loop over numerators in [1, 2)
+__global__ void check_quotients(uint32_t k_first, uint32_t k_count, Report* rep) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;      // < 2^24
+    const uint32_t xb = 0x3F800000u + i;
+    if (!in_midrange(__uint_as_float(xb))) { atomicAdd(&rep->skipped, (unsigned long long)k_count); return; }
+    float y;
+    const float root = root_rn_midrange(__uint_as_float(xb), y);
+    for (uint32_t k = 0; k < k_count; ++k) {
+        const uint32_t ab = 0x3F800000u + k_first + k;
+        const float a = __uint_as_float(ab);
+        const float got = quotient_rn_midrange(a, root, y);
+        const float want = a / root;
+        if (__float_as_uint(got) != __float_as_uint(want)) note(rep, xb, ab, got, want);
+    }
+}
+
+__device__ uint32_t mix(uint32_t v) {          // any well-mixing hash will do here
+    v ^= v >> 16; v *= 0x7FEB352Du; v ^= v >> 15; v *= 0x846CA68Bu; v ^= v >> 16;
+    return v;
+}
+
+// radicands over [2^-64, 2^64), numerators over +-[2^-40, 2^40]
+__global__ void check_sampled(unsigned long long n, uint32_t seed, Report* rep) {
+    for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (unsigned long long)gridDim.x * blockDim.x) {
+        const uint32_t u = mix((uint32_t)i ^ seed), v = mix(u + 0x9E3779B9u + (uint32_t)(i >> 32));
+        const uint32_t xb = 0x1F800000u + (u & 0x3FFFFFFFu);
+        const uint32_t mag = 0x2B800000u + (v % 0x28000001u);      // 2^-40 .. 2^40
+        const uint32_t ab = mag | (v & 0x80000000u);
+        if (!in_midrange(__uint_as_float(xb))) { atomicAdd(&rep->skipped, 1ull); continue; }
+        float y;
+        const float root = root_rn_midrange(__uint_as_float(xb), y);
+        const float a = __uint_as_float(ab);
+        const float got = quotient_rn_midrange(a, root, y);
+        const float want = a / __builtin_sqrtf(__uint_as_float(xb));
+        if (__float_as_uint(got) != __float_as_uint(want)) note(rep, xb, ab, got, want);
+    }
+}
+
+static int finish(const char* what, unsigned long long cases, Report* dev) {
+    Report host;
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipMemcpy(&host, dev, sizeof(host), hipMemcpyDeviceToHost));
+    std::printf("%s: %llu cases (%llu of them not admitted to the short path, skipped), "
+                "%llu mismatches\n", what, cases, host.skipped, host.mismatches);
+    for (unsigned long long i = 0; i < host.mismatches && i < 8; ++i)
+        std::printf("  radicand 0x%08x numerator 0x%08x got 0x%08x expected 0x%08x\n",
+                    host.first[i][0], host.first[i][1], host.first[i][2], host.first[i][3]);
+    std::fflush(stdout);
+    return host.mismatches ? 1 : 0;
+}
+
+int main(int argc, char** argv) {
+    if (argc < 2) { std::fprintf(stderr, "usage: see the header of lambda_check.hip\n"); return 2; }
+    Report* rep = nullptr;
+    CHECK(hipMalloc(&rep, sizeof(Report)));
+    CHECK(hipMemset(rep, 0, sizeof(Report)));
+    if (!std::strcmp(argv[1], "roots")) {
+        const uint32_t first = 0x1F800000u, total = 0x40000000u, step = 1u << 26;
+        for (uint32_t done = 0; done < total; done += step) {
+            hipLaunchKernelGGL(check_roots, dim3(4096), dim3(256), 0, 0, first + done, step, rep);
+            CHECK(hipGetLastError());
+            CHECK(hipDeviceSynchronize());
+        }
+        return finish("roots", total, rep);
+    }
+    if (!std::strcmp(argv[1], "quotients") && argc >= 4) {
+        const unsigned long long k_first = std::strtoull(argv[2], nullptr, 0);
+        const unsigned long long k_count = std::strtoull(argv[3], nullptr, 0);
+        if (k_first + k_count > (1ull << 23) || k_count == 0) { std::fprintf(stderr, "bad range\n"); return 2; }
+        const uint32_t per_launch = 1u << 11;      // 2^24 radicands x 2^11 numerators per launch
+        unsigned long long done = 0;
+        int launches = 0;
+        while (done < k_count) {
+            const uint32_t now = (uint32_t)((k_count - done < per_launch) ? k_count - done : per_launch);
+            hipLaunchKernelGGL(check_quotients, dim3((1u << 24) / 256), dim3(256), 0, 0,
+                               (uint32_t)(k_first + done), now, rep);
+            CHECK(hipGetLastError());
+            CHECK(hipDeviceSynchronize());
+            done += now;
+            if (++launches % 64 == 0) {
+                Report host;
+                CHECK(hipMemcpy(&host, rep, sizeof(host), hipMemcpyDeviceToHost));
+                std::printf("  numerators %llu of %llu done, %llu mismatches so far\n", done, k_count,
+                            host.mismatches);
+                std::fflush(stdout);
+            }
+        }
+        return finish("quotients", (1ull << 24) * k_count, rep);
+    }
+    if (!std::strcmp(argv[1], "sampled") && argc >= 4) {
+        const unsigned long long n = std::strtoull(argv[2], nullptr, 0);
+        const uint32_t seed = (uint32_t)std::strtoull(argv[3], nullptr, 0);
+        hipLaunchKernelGGL(check_sampled, dim3(8192), dim3(256), 0, 0, n, seed, rep);
+        CHECK(hipGetLastError());
+        return finish("sampled", n, rep);
+    }
+    std::fprintf(stderr, "usage: see the header of lambda_check.hip\n");
+    return 2;
+}
