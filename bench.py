@@ -127,6 +127,8 @@ def main() -> int:
     ap.add_argument("--bak-bf16", action="store_true",
                     help="snapshots handed out and kept as bfloat16 (a storage variant; the "
                          "default measures the float32 backups of the configurations)")
+    ap.add_argument("--native-loop", action="store_true",
+                    help="additionally time the same arrivals through dcasgd_run_synth")
     ap.add_argument("--ordered", action="store_true",
                     help="fold workload: after the timed region, time the same steps again "
                          "with the gradients ranked by norm on the device before each fold")
@@ -321,6 +323,20 @@ def main() -> int:
                                     "bytes_per_element_update": fbytes / wl.d,
                                     "note": "synthetic workload only: worker gradient formed in "
                                             "registers inside the push kernel"}
+    if args.native_loop and K == 1 and not sync:
+        # the same arrivals through the library's own event loop (one C call, one fused
+        # launch per arrival)
+        torch.cuda.synchronize()
+        sv.run_synth(arrivals[:n_warm], hd, ws, wl.sigma, wl.seed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sv.run_synth(arrivals[n_warm:n_warm + n_steps], hd, ws, wl.sigma, wl.seed)
+        torch.cuda.synchronize()
+        ne = time.perf_counter() - t0
+        out["native_loop_path"] = {"value": wl.d * n_steps / ne, "unit": "element-updates/s",
+                                   "ms_per_step": 1e3 * ne / n_steps,
+                                   "note": "synthetic workload only: dcasgd_run_synth, worker "
+                                           "fused into the push, launches issued from native code"}
     if args.ordered and sync:
         # norms + ranking + fold over the ranked list: three launches per fold
         fws = B.Server.fold_workspace(dev)

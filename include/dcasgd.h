@@ -274,6 +274,18 @@ int dcasgd_synth_grad(const void* snap, const float* hdiag, const float* wstar,
 int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* wstar,
                       float sigma, uint64_t seed, void* stream);
 
+/*
+ * The event loop of Algorithms 1 and 2 for the synthetic workload, driven from
+ * native code: for e < T, dcasgd_push_synth(h, workers[e], ...), i.e. worker
+ * workers[e] delivers the gradient of its snapshot, the server applies it and
+ * (with DCASGD_PULL_ON_PUSH) hands the new model back.  workers: host array.
+ * The whole list is validated before the first launch; one kernel launch per
+ * arrival and no interpreter between them, which is what matters for small
+ * models whose kernels run a few microseconds.
+ */
+int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdiag,
+                     const float* wstar, float sigma, uint64_t seed, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -40,6 +40,8 @@ _PROTOTYPES = {
                                            C.c_void_p, C.c_void_p]),
     "dcasgd_push_synth": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
                                     C.c_uint64, C.c_void_p]),
+    "dcasgd_run_synth": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.c_size_t, C.c_void_p,
+                                   C.c_void_p, C.c_float, C.c_uint64, C.c_void_p]),
     "dcasgd_pull": (C.c_void_p, [C.c_void_p, C.c_int]),
     "dcasgd_step": (C.c_uint64, [C.c_void_p]),
     "dcasgd_last_error": (C.c_int, [C.c_void_p]),
@@ -255,6 +257,15 @@ class Server:
         _check(load().dcasgd_push_synth(self._h, int(worker), hdiag.data_ptr(), wstar.data_ptr(),
                                         float(sigma), int(seed), _stream_ptr(stream)),
                "dcasgd_push_synth")
+
+    def run_synth(self, workers, hdiag, wstar, sigma: float, seed: int, stream=None) -> None:
+        """push_synth for every entry of ``workers`` in order, looped in native code."""
+        assert hdiag.is_cuda and wstar.is_cuda and hdiag.numel() == wstar.numel() == self.d
+        ws = [int(m) for m in workers]
+        arr = (C.c_int * len(ws))(*ws)
+        _check(load().dcasgd_run_synth(self._h, arr, len(ws), hdiag.data_ptr(), wstar.data_ptr(),
+                                       float(sigma), int(seed), _stream_ptr(stream)),
+               "dcasgd_run_synth")
 
     def sync_fold(self, grads: Sequence, eta_hat: float, stream=None, workspace=None) -> None:
         """Fold J same-snapshot gradients into w (the supplement's synchronous variant).

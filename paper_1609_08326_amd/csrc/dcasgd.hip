@@ -407,6 +407,19 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
     return launched(h);
 }
 
+int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdiag,
+                     const float* wstar, float sigma, uint64_t seed, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (!workers && T > 0) return fail(h, DCASGD_EINVAL);
+    for (size_t e = 0; e < T; ++e)
+        if (workers[e] < 0 || workers[e] >= h->M) return fail(h, DCASGD_EINVAL);
+    if (h->t + T > 0xFFFFFFFFull) return fail(h, DCASGD_EINVAL);
+    for (size_t e = 0; e < T; ++e)
+        if (int rc = dcasgd_push_synth(h, workers[e], hdiag, wstar, sigma, seed, stream)) return rc;
+    return DCASGD_OK;
+}
+
 // Both fold entry points: with a workspace the gradients are first ranked by
 // norm on the device and folded in that order, without one the caller's order
 // stands.

@@ -6,6 +6,7 @@ import sys
 import numpy as np
 import pytest
 
+import oracle
 from paper_1609_08326_amd import workloads as W
 
 from gpu_harness import DeviceRun, assert_same_bits, oracle_run
@@ -109,3 +110,29 @@ def test_vector_longer_than_4_gib():
     assert_same_bits(sv.bak[0][ii].cpu().numpy(), ref.bak(0), "huge bak")
     # nothing beyond the sample is left untouched: w moved everywhere h is not tiny
     assert int((sv.w == 0).sum().item()) < wl.d // 1000
+
+
+def test_native_event_loop_matches_oracle_and_validates_first():
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = W.CONFIGS[1].replace(T=120)
+    hd_h, ws_h, order = wl.hdiag(), wl.wstar(), wl.arrivals()
+    hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
+                  wl.eps, pull_on_push=True)
+    bad = [int(m) for m in order[:10]] + [wl.M]
+    with pytest.raises(B.DcasgdError):
+        sv.run_synth(bad, hd, ws, wl.sigma, wl.seed)
+    torch.cuda.synchronize()
+    assert sv.t == 0                                   # nothing was launched for the bad list
+    sv.run_synth(order[:50], hd, ws, wl.sigma, wl.seed)
+    sv.run_synth([], hd, ws, wl.sigma, wl.seed)
+    sv.run_synth(order[50:], hd, ws, wl.sigma, wl.seed)
+    torch.cuda.synchronize()
+    ref = oracle.Server(wl.w0(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+    ref.run(order, hd_h, ws_h, wl.sigma, wl.seed, nthreads=8)
+    assert sv.t == ref.t == len(order)
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "native loop w")
+    assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "native loop ms")
+    for m in range(wl.M):
+        assert_same_bits(sv.bak[m, : wl.d].cpu().numpy(), ref.bak(m), "native loop bak[%d]" % m)
