@@ -200,3 +200,53 @@ def test_ordered_fold_full_size():
     ref.sync_fold(g[order], wl.eta * wl.K)
     assert_same_bits(sv.w.cpu().numpy(), ref.w(), "ordered fold w (full)")
     assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "ordered fold ms (full)")
+
+
+def test_ordered_fold_replays_from_a_captured_graph():
+    """Norms, ranking and fold are three plain launches with no host round trip and no
+    memset, so a round of J worker gradients plus the ordered fold can be captured into a
+    HIP graph; every replay must land on the oracle's bits (with eager work in between)."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = W.get("fold").replace(d=300007, K=6)
+    hd_h, ws_h, w0 = wl.hdiag(), wl.wstar(), wl.w0()
+    hd, wst = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    side = torch.cuda.Stream()
+    gbuf = [torch.empty(wl.d, device="cuda") for _ in range(wl.K)]
+    fws = B.Server.fold_workspace()
+    torch.cuda.synchronize()
+
+    def one_round(sv):
+        for j in range(wl.K):
+            B.synth_grad(sv.w, hd, wst, wl.sigma, wl.seed, j, gbuf[j])
+        sv.sync_fold(gbuf, wl.eta * wl.K, workspace=fws)
+
+    ref = oracle.Server(w0, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+
+    def one_round_ref():
+        w_t = ref.w()
+        g = np.stack([oracle.synth_grad(w_t, hd_h, ws_h, wl.sigma, wl.seed, j) for j in range(wl.K)])
+        order = np.argsort(oracle.grad_sqnorms(g), kind="stable")
+        ref.sync_fold(g[order], wl.eta * wl.K)
+        return order
+
+    with torch.cuda.stream(side):
+        sv = B.Server(torch.from_numpy(w0).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+        one_round(sv)                                   # eager warm-up round
+    side.synchronize()
+    one_round_ref()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        one_round(sv)                                   # captured, not run
+    other = torch.zeros(1 << 18, device="cuda")
+    for r in range(3):
+        say("ordered fold graph replay %d" % r)
+        graph.replay()
+        torch.cuda.synchronize()
+        order = one_round_ref()
+        perm = B.Server.fold_order(fws, wl.K)[1]
+        assert perm.tolist() == order.tolist(), (r, perm, order)
+        assert_same_bits(sv.w.cpu().numpy(), ref.w(), "replay %d w" % r)
+        assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "replay %d ms" % r)
+        other.add_(1.0)
+        torch.cuda.synchronize()
