@@ -350,3 +350,38 @@ def test_per_launch_timing_counts_launches_and_changes_nothing():
     sv2.push(1, g)
     assert sv2.timing_read_each(capacity=1).size == 1     # a short buffer still ends the interval
     assert sv2.timing_read() == (0.0, 0)
+
+
+def test_two_servers_on_two_streams_do_not_disturb_each_other():
+    """Handles share nothing: two servers driven alternately on two streams, with no
+    synchronisation between the streams, each end on the oracle's bits."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wls = [small(150001, M=3, T=40, mode=W.MODE_A, seed=91), small(99991, M=5, T=40, mode=W.MODE_C, seed=92)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    svs, inputs, gbufs = [], [], []
+    torch.cuda.synchronize()
+    for wl, st in zip(wls, streams):
+        with torch.cuda.stream(st):
+            hd, ws = torch.from_numpy(wl.hdiag()).cuda(), torch.from_numpy(wl.wstar()).cuda()
+            svs.append(B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode,
+                                wl.ema_m, wl.eps, pull_on_push=True))
+            inputs.append((hd, ws))
+            gbufs.append(torch.empty(wl.d, device="cuda"))
+    torch.cuda.synchronize()
+    orders = [wl.arrivals() for wl in wls]
+    for t in range(40):
+        for i, (wl, st) in enumerate(zip(wls, streams)):
+            with torch.cuda.stream(st):
+                m = int(orders[i][t])
+                if t % 3 == 0:
+                    svs[i].push_synth(m, *inputs[i], wl.sigma, wl.seed)
+                else:
+                    B.synth_grad(svs[i].snapshot(m), *inputs[i], wl.sigma, wl.seed, t, gbufs[i])
+                    svs[i].push(m, gbufs[i])
+    torch.cuda.synchronize()
+    for i, wl in enumerate(wls):
+        ref = oracle_run(wl, wl.hdiag(), wl.wstar(), orders[i], nthreads=4)
+        assert_same_bits(svs[i].w.cpu().numpy(), ref.w(), "server %d w" % i)
+        for m in range(wl.M):
+            assert_same_bits(svs[i].bak[m, : wl.d].cpu().numpy(), ref.bak(m), "server %d bak[%d]" % (i, m))
