@@ -385,3 +385,43 @@ def test_two_servers_on_two_streams_do_not_disturb_each_other():
         assert_same_bits(svs[i].w.cpu().numpy(), ref.w(), "server %d w" % i)
         for m in range(wl.M):
             assert_same_bits(svs[i].bak[m, : wl.d].cpu().numpy(), ref.bak(m), "server %d bak[%d]" % (i, m))
+
+
+def test_radicand_that_the_short_square_root_must_not_take():
+    """MeanSquare + eps = 1 - 2^-24 (all-ones significand, even exponent field) is the one
+    radicand pattern whose root lies 2^-50 below a rounding midpoint; the kernels send it
+    down the general expansion.  Built here on purpose: m = 0, eps = 1 - 2^-23 and
+    g = +-2^-12 give exactly that radicand; lambda0 = 2^24, eta = 1 and a model of the
+    gradient's own size make the last bit of lambda visible in w: with a root of exactly 1
+    about half of those parameters would come out different (checked below on the host)."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    F = np.float32
+    rng = np.random.default_rng(41)
+    d = 70003
+    eps, lam0, eta = F(1.0) - F(2.0 ** -23), F(2.0 ** 24), F(1.0)
+    w0 = (F(2.0 ** -12) * rng.standard_normal(d)).astype(F)
+    sv = B.Server(torch.from_numpy(w0).cuda(), 2, float(eta), float(lam0), B.MODE_A, 0.0, float(eps))
+    ref = oracle.Server(w0, 2, float(eta), float(lam0), oracle.MODE_A, 0.0, float(eps))
+    first = (F(2.0 ** -12) * rng.standard_normal(d)).astype(F)    # moves w away from the backups
+    sv.push(0, torch.from_numpy(first).cuda())
+    ref.push(0, first)
+    w1 = ref.w().copy()
+    hit = rng.random(d) < 0.5
+    g = np.where(hit, F(2.0 ** -12) * rng.choice([-1.0, 1.0], d),
+                 F(2.0 ** -12) * rng.standard_normal(d)).astype(F)
+    sv.push(1, torch.from_numpy(g).cuda())                        # worker 1 still holds w0
+    ref.push(1, g)
+    torch.cuda.synchronize()
+    under = (ref.ms() + eps).astype(F)
+    assert np.all(under[hit].view(np.uint32) == 0x3F7FFFFF)       # the pattern was really produced
+    assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "ms")
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "w with the excluded radicand in every wave")
+    # what a root of exactly 1 for those radicands would have given
+    lam = np.where(hit, lam0, lam0 / np.sqrt(under)).astype(F)
+    g2 = g * g
+    c1 = lam * g2
+    c2 = c1 * (w1 - w0)
+    gd = g + c2
+    wrong = (w1 - eta * gd).astype(F)
+    assert int(np.sum(wrong.view(np.uint32) != ref.w().view(np.uint32))) > hit.sum() // 4
