@@ -425,3 +425,46 @@ def test_radicand_that_the_short_square_root_must_not_take():
     gd = g + c2
     wrong = (w1 - eta * gd).astype(F)
     assert int(np.sum(wrong.view(np.uint32) != ref.w().view(np.uint32))) > hit.sum() // 4
+
+
+def test_every_bit_of_lambda_reaches_the_model():
+    """In the benchmark configurations the compensation term is small next to g, so an
+    error in the last bit of lambda would rarely reach w.  Here it always does: m = 0 and
+    eps = 0 make lambda = lambda0/|g|, lambda0 = 2^24 makes the compensation term dominate
+    the step, and the scales run over forty binades, so square root, quotient and the three
+    products that follow are compared on every significand they produce (the host check at
+    the end shows that nudging lambda by one ulp changes most parameters)."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    F = np.float32
+    rng = np.random.default_rng(43)
+    d = 400003
+    scale = np.exp2(rng.integers(-30, 11, d)).astype(F)
+    w0 = (scale * rng.standard_normal(d)).astype(F)
+    lam0 = F(2.0 ** 24)
+    sv = B.Server(torch.from_numpy(w0).cuda(), 2, 1.0, float(lam0), B.MODE_A, 0.0, 0.0)
+    ref = oracle.Server(w0, 2, 1.0, float(lam0), oracle.MODE_A, 0.0, 0.0)
+    first = (scale * rng.standard_normal(d)).astype(F)
+    sv.push(0, torch.from_numpy(first).cuda())
+    ref.push(0, first)
+    w1 = ref.w().copy()
+    g = (scale * rng.standard_normal(d)).astype(F)
+    g[g == 0] = scale[g == 0]
+    sv.push(1, torch.from_numpy(g).cuda())                        # worker 1 still holds w0
+    ref.push(1, g)
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(ref.w()))
+    assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "ms")
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "w")
+    # sensitivity of this input: lambda one ulp up
+    g2 = g * g
+    lam = (lam0 / np.sqrt(g2)).astype(F)
+    nudged = (lam.view(np.uint32) + 1).view(F)
+    out = []
+    for L in (lam, nudged):
+        c1 = L * g2
+        c2 = c1 * (w1 - w0)
+        gd = g + c2
+        out.append((w1 - gd).astype(F))
+    assert np.array_equal(out[0].view(np.uint32), ref.w().view(np.uint32))
+    assert int(np.sum(out[0].view(np.uint32) != out[1].view(np.uint32))) > d // 3
