@@ -78,7 +78,30 @@ def build_checker(force: bool = True, verbose: bool = False) -> str:
     return CHECKER
 
 
+CLIENT_SRC = os.path.join(CSRC, "abi_client.c")
+CLIENT = os.path.join(_PKG, "abi_client")
+
+
+def build_client(force: bool = True, verbose: bool = False) -> str:
+    """Build the plain-C client of the ABI (compiled as C99, linked against the library)."""
+    deps = [CLIENT_SRC, os.path.join(os.path.dirname(_PKG), "include", "dcasgd.h")]
+    stale = (not os.path.exists(CLIENT)) or \
+        any(os.path.getmtime(CLIENT) < os.path.getmtime(p) for p in deps)
+    if force or stale:
+        tmp = CLIENT + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-O1", "-D__HIP_PLATFORM_AMD__",
+               "-I", os.path.join(os.path.dirname(_PKG), "include"), "-I", "/opt/rocm/include",
+               CLIENT_SRC, "-o", tmp, "-L", _PKG, "-ldcasgd", "-L", "/opt/rocm/lib", "-lamdhip64",
+               "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib"]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        os.replace(tmp, CLIENT)
+    return CLIENT
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))
     print(build_probe(force=True, verbose=True))
     print(build_checker(force=True, verbose=True))
+    print(build_client(force=True, verbose=True))
