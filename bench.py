@@ -79,6 +79,31 @@ def cpu_baseline(wl, target_s: float, bak_bf16: bool = False):
         sv.run(order, hd, ws, wl.sigma, wl.seed, as_bf16=wl.grad_bf16, nthreads=threads)
         return time.perf_counter() - t0
 
+    def timed_server_only(T):
+        """push + pull per arrival on one thread, gradients formed beforehand (untimed)."""
+        order = wl.replace(T=-(-T // wl.K) * wl.K).arrivals()[:T]
+        sv = oracle.Server(np.zeros(n, dtype=np.float32), wl.M, wl.eta, wl.lambda0, wl.mode,
+                           wl.ema_m, wl.eps)
+        if bak_bf16:
+            sv.set_backup_bf16()
+        spent = 0.0
+        for t, m in enumerate(order):
+            g = oracle.synth_grad(sv.bak(int(m)), hd, ws, wl.sigma, wl.seed, t, as_bf16=wl.grad_bf16)
+            t0 = time.perf_counter()
+            sv.push(int(m), g)
+            sv.pull(int(m))
+            spent += time.perf_counter() - t0
+        return spent
+
+    def cpu_model():
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+        except OSError:
+            pass
+        return "unknown"
+
     probe = 8
     dt = timed(probe, cores)
     T = int(max(probe, min(20000, target_s / max(dt / probe, 1e-9))))
@@ -86,7 +111,13 @@ def cpu_baseline(wl, target_s: float, bak_bf16: bool = False):
     # the oracle as specified is sequential: one thread, a quarter of the time budget
     T1 = int(max(1, min(T, 0.25 * target_s / max(dt / T * cores, 1e-9))))
     dt1 = timed(T1, 1)
+    dts = timed_server_only(T1)
     return {"value": n * T / dt, "unit": "element-updates/s", "cores": cores, "kind": "oracle",
+            "cpu": cpu_model(), "host_threads_available": len(os.sched_getaffinity(0)),
+            "server_only_one_core": {"value": n * T1 / dts, "unit": "element-updates/s",
+                                     "sample": "%d arrivals, push + pull only (the gradient is "
+                                               "formed outside the timed calls), 1 thread, %.1f s"
+                                               % (T1, dts)},
             "sample": "first %d of %d elements, %d arrivals in the workload's order, "
                       "gradient+push+pull per arrival, %d threads over element chunks, %.1f s"
                       % (n, wl.d, T, cores, dt),
