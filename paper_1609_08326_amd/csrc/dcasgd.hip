@@ -312,8 +312,9 @@ int dcasgd_init(dcasgd_t h, void* stream) {
     h->stream = s;
     h->t = 0;
     h->fresh_at.assign((size_t)h->M, 0);
-    h->ready = true;
-    return launched(h);
+    const int rc = launched(h);
+    h->ready = rc == DCASGD_OK;       // a handle whose initial copies did not launch stays unusable
+    return rc;
 }
 
 int dcasgd_push(dcasgd_t h, int worker, const void* grad, void* stream) {

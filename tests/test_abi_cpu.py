@@ -132,3 +132,24 @@ def test_header_is_plain_c_and_binding_matches_its_arity(tmp_path):
     assert seen == len(binding._PROTOTYPES)
     assert binding.FOLD_WS_BYTES == int(re.search(r"#define DCASGD_FOLD_WS_BYTES (\d+)", text).group(1))
     assert binding.MAX_K == int(re.search(r"#define DCASGD_MAX_K (\d+)", text).group(1))
+
+
+def test_without_a_gpu_launching_calls_report_the_runtime_error_and_nothing_becomes_ready(lib):
+    """No GPU in the CPU test environment: dcasgd_init must come back with the HIP error
+    code (not crash, not pretend), and the handle must then refuse pushes as not ready.
+    Skipped where a GPU is present."""
+    import ctypes as C
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    from paper_1609_08326_amd import binding as B
+    h = lib.dcasgd_create(1000, 2, 0.1, 0.04, B.MODE_C, 0.0, 0.0)
+    # host memory stands in for device memory: nothing can be launched here anyway
+    buf = (C.c_float * (1024 * 4 + 64))()
+    base = (C.addressof(buf) + 255) // 256 * 256
+    assert lib.dcasgd_bind(h, base, base + 4096, 1024, None) == B.OK
+    assert lib.dcasgd_init(h, None) == B.EHIP
+    assert lib.dcasgd_push(h, 0, base + 3 * 4096, None) == B.ESTATE
+    assert lib.dcasgd_pull(h, 0) is None
+    assert lib.dcasgd_last_error(h) == B.ESTATE
+    assert lib.dcasgd_destroy(h) == B.OK
