@@ -176,6 +176,7 @@ def main() -> int:
     from paper_1609_08326_amd import workloads as W
 
     wl = W.get(args.workload)
+    own_mode = wl.mode
     if args.variant == "c":
         wl = wl.replace(name=wl.name + "+c", mode=W.MODE_C, lambda0=0.04, ema_m=0.0, eps=0.0)
     elif args.variant == "a":
@@ -269,6 +270,8 @@ def main() -> int:
     bpu = algorithmic_bytes_per_update(wl, unfused, args.bak_bf16)
     kname = ("sync_fold_J%d" % K if sync else "push_batch_K%d" % K if batched
              else "push_then_pull" if unfused else "push_fused")
+    if wl.mode != own_mode:
+        kname += "_" + args.variant      # another kernel than the workload's own: its own profile
     if args.bak_bf16 and not sync:
         kname += "_bak16"
     out = {
