@@ -71,6 +71,8 @@ def lib() -> C.CDLL:
         L.oracle_set_backup_bf16.restype = None
         L.oracle_set_eta.argtypes = [vp, C.c_float]
         L.oracle_set_eta.restype = None
+        L.oracle_set_lambda.argtypes = [vp, C.c_float]
+        L.oracle_set_lambda.restype = None
         L.oracle_push.argtypes = [vp, C.c_int, f32p]
         L.oracle_push.restype = C.c_int
         L.oracle_pull.argtypes = [vp, C.c_int]
@@ -181,6 +183,10 @@ class Server:
 
     def set_eta(self, eta: float) -> None:
         lib().oracle_set_eta(self._h, float(eta))
+
+    def set_lambda(self, lambda0: float) -> None:
+        """lambda_t of Algorithm 2 for all later pushes (lambda_0 in the adaptive variant)."""
+        lib().oracle_set_lambda(self._h, float(lambda0))
 
     def set_backup_bf16(self, on: bool = True) -> None:
         """Snapshots travel and are kept as bfloat16 (round to nearest even of w)."""

@@ -390,6 +390,10 @@ void oracle_set_backup_bf16(void* h, int on) {
 // Learning-rate schedule (Section 6 divides eta by ten at fixed epochs).
 void oracle_set_eta(void* h, float eta) { static_cast<Server*>(h)->eta = eta; }
 
+// Algorithm 2 takes a time-indexed lambda_t as input: lambda (DC-ASGD-c) or
+// lambda_0 (DC-ASGD-a) may be changed between pushes.
+void oracle_set_lambda(void* h, float lambda0) { static_cast<Server*>(h)->lambda0 = lambda0; }
+
 // Algorithm 2 "receive g_m": g has n floats (already widened if it travelled
 // as bf16).
 int oracle_push(void* h, int worker, const float* g) {

@@ -385,3 +385,30 @@ def test_set_eta_changes_later_pushes_only():
         sv.push(0, g)
         w = (w - (F32(eta) * g).astype(F32)).astype(F32)
         assert np.array_equal(sv.w(), w), step
+
+
+def test_time_indexed_lambda():
+    """Algorithm 2 lists lambda_t as an input: changing it between pushes must equal
+    running each stretch with a server built for that value (same state carried over),
+    and lambda = 0 for a stretch must make that stretch plain ASGD."""
+    rng = np.random.default_rng(12)
+    n, M = 500, 3
+    w0 = rng.standard_normal(n).astype(F32)
+    gs = rng.standard_normal((12, n)).astype(F32)
+    order = rng.integers(0, M, 12)
+    sv = oracle.Server(w0, M, 0.1, 0.04, MODE_C)
+    for t in range(12):
+        if t == 4:
+            sv.set_lambda(0.0)
+        if t == 8:
+            sv.set_lambda(0.5)
+        before = sv.w().copy()
+        bak = sv.bak(int(order[t])).copy()
+        sv.push(int(order[t]), gs[t])
+        lam = F32(0.04) if t < 4 else F32(0.0) if t < 8 else F32(0.5)
+        g = gs[t]
+        expect = before - F32(0.1) * (g + (lam * (g * g)) * (before - bak))
+        assert np.array_equal(sv.w(), expect.astype(F32)), t
+        if 4 <= t < 8:
+            assert np.array_equal(sv.w(), (before - F32(0.1) * g).astype(F32))
+        sv.pull(int(order[t]))
