@@ -235,6 +235,12 @@ int dcasgd_timing_read_each(dcasgd_t h, float* each_ms, size_t capacity, uint64_
 int dcasgd_set_eta(dcasgd_t h, float eta);
 
 /*
+ * Algorithm 2 lists a time-indexed lambda_t as its input: change lambda
+ * (MODE_C) or lambda_0 of Eq. 18 (MODE_A) for all later pushes.  Must be finite.
+ */
+int dcasgd_set_lambda(dcasgd_t h, float lambda0);
+
+/*
  * Launch shape used by this handle's kernels.  threads: 64..512, a multiple
  * of 64; items: float4 groups per thread, one of 1, 2, 4; max_blocks: 0 = one
  * block per tile, otherwise blocks loop over tiles; streaming: 0 = plain

@@ -56,6 +56,7 @@ _PROTOTYPES = {
     "dcasgd_timing_read_each": (C.c_int, [C.c_void_p, C.POINTER(C.c_float), C.c_size_t,
                                           C.POINTER(C.c_uint64)]),
     "dcasgd_set_eta": (C.c_int, [C.c_void_p, C.c_float]),
+    "dcasgd_set_lambda": (C.c_int, [C.c_void_p, C.c_float]),
     "dcasgd_set_launch": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]),
     "dcasgd_synth_grad": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_uint64,
                                     C.c_uint32, C.c_void_p, C.c_int, C.c_size_t, C.c_void_p,
@@ -230,6 +231,10 @@ class Server:
     def set_eta(self, eta: float) -> None:
         """Learning rate of all later pushes (step schedules)."""
         _check(load().dcasgd_set_eta(self._h, float(eta)), "dcasgd_set_eta")
+
+    def set_lambda(self, lambda0: float) -> None:
+        """lambda_t of Algorithm 2 for all later pushes (lambda_0 in the adaptive variant)."""
+        _check(load().dcasgd_set_lambda(self._h, float(lambda0)), "dcasgd_set_lambda")
 
     def set_launch(self, threads: int = 0, items: int = 0, max_blocks: int = 0,
                    streaming: int = 2) -> None:

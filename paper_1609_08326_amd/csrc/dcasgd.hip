@@ -671,6 +671,15 @@ int dcasgd_set_eta(dcasgd_t h, float eta) {
     return DCASGD_OK;
 }
 
+int dcasgd_set_lambda(dcasgd_t h, float lambda0) {
+    if (!h) return DCASGD_EINVAL;
+    if (!std::isfinite(lambda0)) return fail(h, DCASGD_EINVAL);
+    h->hp.lambda0 = lambda0;   // passed by value with every launch, like eta
+    const float mag = std::fabs(lambda0);
+    h->hp.lambda_midrange = (mag >= 0x1p-40f && mag <= 0x1p40f) ? 1 : 0;
+    return DCASGD_OK;
+}
+
 int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming) {
     if (!h) return DCASGD_EINVAL;
     if (threads > 0 && !valid_threads(threads)) return fail(h, DCASGD_EINVAL);

@@ -76,8 +76,8 @@ def test_random_call_sequence(seed):
         return gt.float().numpy(), [gt[j].contiguous().cuda() for j in range(n)]
 
     ops = ["push", "batch", "batch_repeat", "pull", "fold", "fold_ranked", "push_synth",
-           "worker_then_push", "eta", "momentum"]
-    weights = np.array([4, 2, 1, 2, 1, 1, 2, 1, 1, 1], dtype=float)
+           "worker_then_push", "eta", "momentum", "lambda"]
+    weights = np.array([4, 2, 1, 2, 1, 1, 2, 1, 1, 1, 1], dtype=float)
     trace = []
     for step in range(90):
         op = str(rng.choice(ops, p=weights / weights.sum()))
@@ -140,6 +140,11 @@ def test_random_call_sequence(seed):
             eta = float(np.float32(rng.choice([0.1, 0.05, 0.01, 0.002])))
             sv.set_eta(eta)
             ref.set_eta(eta)
+        elif op == "lambda":
+            # includes 0 (plain ASGD for a stretch) and values outside the short-form window
+            lam = float(np.float32(rng.choice([0.0, 0.01, 0.04, 1.0, 2.0, 2.0 ** -45, -0.5])))
+            sv.set_lambda(lam)
+            ref.set_lambda(lam)
         elif op == "momentum":
             mu = float(np.float32(rng.choice([0.0, 0.5, 0.9])))
             torch.cuda.synchronize()          # the old velocity buffer is released here
