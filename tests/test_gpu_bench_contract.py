@@ -36,7 +36,7 @@ def test_default_workload_line():
     assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12
     assert 0.5 < r["frac"] < 1.0, r                      # a streaming kernel on HBM3E
-    assert r["launches_timed"] == 12 and r["timed_by"].startswith("HIP events")
+    assert r["launches_timed"] == 12 and r["timed_by"].startswith("HIP ")
     assert r["traffic"] is None or 0.9 < r["traffic"] / r["algorithmic_bytes_per_launch"] < 1.1
     c = out["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and "sample" in c
