@@ -468,3 +468,48 @@ def test_every_bit_of_lambda_reaches_the_model():
         out.append((w1 - gd).astype(F))
     assert np.array_equal(out[0].view(np.uint32), ref.w().view(np.uint32))
     assert int(np.sum(out[0].view(np.uint32) != out[1].view(np.uint32))) > d // 3
+
+
+def test_config2_every_element_for_a_stretch_of_pushes():
+    """Configuration 2 at full size and in bench.py's launch shape, the oracle on ALL
+    25.6 M parameters (16 host threads over element chunks) for the first 48 arrivals:
+    w, MeanSquare and all sixteen backups, every word."""
+    wl = W.CONFIGS[2].replace(T=48)
+    say("every element of %s for %d arrivals" % (wl.name, wl.T))
+    run = DeviceRun(wl)
+    ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=16)
+    compare(run, ref, tag="cfg2 in full")
+
+
+def test_config4_every_element_for_a_few_pushes():
+    """Configuration 4 (138 M parameters, bf16 gradients): w, MeanSquare and the backups
+    of the workers that pushed, every word, for the first 6 arrivals."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = W.CONFIGS[4].replace(T=6)
+    hd_h, ws_h, order = wl.hdiag(), wl.wstar(), wl.arrivals()
+    say("every element of %s for %d arrivals %s" % (wl.name, wl.T, order.tolist()))
+    hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
+                  wl.eps, grad_bf16=True, pull_on_push=True)
+    g = torch.empty(wl.d, dtype=torch.bfloat16, device="cuda")
+    for t, m in enumerate(order):
+        B.synth_grad(sv.snapshot(int(m)), hd, ws, wl.sigma, wl.seed, t, g)
+        sv.push(int(m), g)
+    torch.cuda.synchronize()
+    ref = oracle.Server(wl.w0(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+    ref.run(order, hd_h, ws_h, wl.sigma, wl.seed, as_bf16=True, nthreads=16)
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "cfg4 w in full")
+    assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "cfg4 ms in full")
+    for m in sorted(set(int(x) for x in order)):
+        assert_same_bits(sv.bak[m, : wl.d].cpu().numpy(), ref.bak(m), "cfg4 bak[%d] in full" % m)
+
+
+def test_config3_every_element_for_two_queues():
+    """Configuration 3 (queues of 16 through the fused queue kernel, 64-thread blocks as
+    bench.py runs it): every word of w, MeanSquare and the backups after two queues."""
+    wl = W.CONFIGS[3].replace(T=32)
+    say("every element of %s for %d arrivals" % (wl.name, wl.T))
+    run = DeviceRun(wl, batched=True)
+    ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, nthreads=16)
+    compare(run, ref, tag="cfg3 in full")
