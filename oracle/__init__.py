@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
         L.oracle_get_bak.restype = C.c_int
         L.oracle_grad_sqnorms.argtypes = [f32p, C.c_int, C.c_size_t, C.POINTER(C.c_double)]
         L.oracle_grad_sqnorms.restype = None
+        L.oracle_sync_fold_part.argtypes = [vp, f32p, C.c_int, C.c_int, C.c_float, f32p]
+        L.oracle_sync_fold_part.restype = C.c_int
         L.oracle_sync_fold.argtypes = [vp, f32p, C.c_int, C.c_float]
         L.oracle_sync_fold.restype = C.c_int
         L.oracle_synth_grad.argtypes = [f32p, f32p, f32p, C.c_float, C.c_uint64, C.c_uint32,
@@ -220,6 +222,16 @@ class Server:
         assert g.ndim == 2 and g.shape[1] == self.n
         if lib().oracle_sync_fold(self._h, _fp(g), int(g.shape[0]), float(eta_hat)) != 0:
             raise ValueError("sync_fold needs at least one gradient")
+
+    def sync_fold_part(self, grads, J_total: int, eta_hat: float, anchor) -> None:
+        """Some of the J_total gradients of one fold (rows of ``grads``), compensated against
+        ``anchor``, the model the fold started from."""
+        g = np.ascontiguousarray(grads, dtype=np.float32)
+        a = _f32(anchor).ravel()
+        assert g.ndim == 2 and g.shape[1] == self.n and a.size == self.n
+        if lib().oracle_sync_fold_part(self._h, _fp(g), int(g.shape[0]), int(J_total),
+                                       float(eta_hat), _fp(a)) != 0:
+            raise ValueError("bad part of a fold")
 
     def w(self) -> np.ndarray:
         out = np.zeros(self.n, dtype=np.float32)

@@ -464,6 +464,22 @@ int oracle_sync_fold(void* h, const float* g, int J, float eta_hat) {
     return 0;
 }
 
+// The same fold delivered in parts (more same-snapshot gradients than one call
+// takes): Jc of the J_total gradients, compensated against the model the whole
+// fold started from, which the caller kept in `anchor` (n floats).  The step is
+// eta_hat / J_total, formed once in binary32 as in the undivided fold.
+int oracle_sync_fold_part(void* h, const float* g, int Jc, int J_total, float eta_hat,
+                          const float* anchor) {
+    Server& sv = *static_cast<Server*>(h);
+    if (Jc < 1 || J_total < Jc || !g || !anchor) return -1;
+    KeepDenormals guard;
+    const float step = eta_hat / (float)J_total;
+    for (size_t i = 0; i < sv.n; ++i)
+        for (int j = 0; j < Jc; ++j) push_elem(sv, step, g[(size_t)j * sv.n + i], anchor[i], i);
+    sv.t += (uint64_t)Jc;
+    return 0;
+}
+
 // Synthetic worker gradient taken at an arbitrary snapshot (n floats each).
 void oracle_synth_grad(const float* snap, const float* hdiag, const float* wstar,
                        float sigma, uint64_t seed, uint32_t push_idx,

@@ -147,3 +147,34 @@ def test_smallest_first_keeps_the_running_model_closer_to_the_snapshot():
     asc, desc = path_distances(g[order]), path_distances(g[order[::-1]])
     assert np.all(asc[:-1] <= desc[:-1] + 1e-9)
     assert abs(asc[-1] - desc[-1]) < 1e-4            # same end point without compensation
+
+
+@pytest.mark.parametrize("mode", [MODE_C, MODE_A])
+def test_a_fold_delivered_in_parts_is_the_undivided_fold(mode):
+    """J = 40 same-snapshot gradients in parts of 16, 16 and 8 against the kept w_t must
+    leave the bits of the one-call fold; with the running model as anchor (a mistake the
+    interface invites) they must not."""
+    rng = np.random.default_rng(21)
+    n, J = 700, 40
+    w0 = rng.standard_normal(n).astype(F32)
+    g = (0.3 * rng.standard_normal((J, n))).astype(F32)
+    lam0 = 2.0 if mode == MODE_A else 0.04
+    whole = oracle.Server(w0, 1, 0.1, lam0, mode, 0.95, 1e-7)
+    whole.sync_fold(g, 2.0)
+    parts = oracle.Server(w0, 1, 0.1, lam0, mode, 0.95, 1e-7)
+    anchor = parts.w().copy()
+    for lo, hi in ((0, 16), (16, 32), (32, 40)):
+        parts.sync_fold_part(g[lo:hi], J, 2.0, anchor)
+    assert parts.t == whole.t == J
+    assert parts.w().tobytes() == whole.w().tobytes()
+    assert parts.ms().tobytes() == whole.ms().tobytes()
+    wrong = oracle.Server(w0, 1, 0.1, lam0, mode, 0.95, 1e-7)
+    for lo, hi in ((0, 16), (16, 32), (32, 40)):
+        wrong.sync_fold_part(g[lo:hi], J, 2.0, wrong.w())
+    assert wrong.w().tobytes() != whole.w().tobytes()
+    # one part that is the whole fold, anchored at the current model, is sync_fold itself
+    single = oracle.Server(w0, 1, 0.1, lam0, mode, 0.95, 1e-7)
+    single.sync_fold_part(g[:16], 16, 0.8, single.w())
+    ref = oracle.Server(w0, 1, 0.1, lam0, mode, 0.95, 1e-7)
+    ref.sync_fold(g[:16], 0.8)
+    assert single.w().tobytes() == ref.w().tobytes()
