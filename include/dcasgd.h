@@ -149,6 +149,19 @@ int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float 
                              void* workspace, void* stream);
 
 /*
+ * The same fold delivered in parts, for more same-snapshot gradients than one
+ * call takes (large mini-batch SSGD runs on many workers): J of the J_total
+ * gradients are applied with the step eta_hat/J_total and compensated against
+ * kept_w, the model the whole fold started from (w_t), which the caller kept:
+ * device pointer, d floats, 16-byte aligned, not w, ms or the velocity; a
+ * float32 backup row qualifies, so dcasgd_pull of a spare worker before the
+ * first part is one way to keep it.  Parts applied in sequence leave the bits
+ * of the undivided fold.  t advances by J.
+ */
+int dcasgd_sync_fold_part(dcasgd_t h, const void* const* grads, int J, int J_total,
+                          float eta_hat, const float* kept_w, void* stream);
+
+/*
  * Algorithm 2, "pull request": w_bak(worker) <- w, enqueued on the stream of
  * the most recent init/push on this handle, and returns the device pointer of
  * that backup row, which is what "send w_t back to worker m" hands over.  If

@@ -36,6 +36,8 @@ _PROTOTYPES = {
                                     C.c_int, C.c_void_p]),
     "dcasgd_sync_fold": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
                                    C.c_void_p]),
+    "dcasgd_sync_fold_part": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_int,
+                                        C.c_float, C.c_void_p, C.c_void_p]),
     "dcasgd_sync_fold_ordered": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
                                            C.c_void_p, C.c_void_p]),
     "dcasgd_push_synth": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
@@ -290,6 +292,20 @@ class Server:
         _check(load().dcasgd_sync_fold_ordered(self._h, ga, J, float(eta_hat),
                                                workspace.data_ptr(), _stream_ptr(stream)),
                "dcasgd_sync_fold_ordered")
+
+    def sync_fold_part(self, grads: Sequence, J_total: int, eta_hat: float, kept_w,
+                       stream=None) -> None:
+        """Some of the J_total gradients of one fold, compensated against ``kept_w``, the
+        caller's copy of the model the fold started from (a float32 backup row will do)."""
+        J = len(grads)
+        for g in grads:
+            assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
+        import torch
+        assert kept_w.is_cuda and kept_w.dtype == torch.float32 and kept_w.numel() == self.d
+        ga = (C.c_void_p * J)(*[g.data_ptr() for g in grads])
+        _check(load().dcasgd_sync_fold_part(self._h, ga, J, int(J_total), float(eta_hat),
+                                            kept_w.data_ptr(), _stream_ptr(stream)),
+               "dcasgd_sync_fold_part")
 
     @staticmethod
     def fold_workspace(device="cuda"):

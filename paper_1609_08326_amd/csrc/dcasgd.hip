@@ -424,12 +424,25 @@ int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdia
 // Both fold entry points: with a workspace the gradients are first ranked by
 // norm on the device and folded in that order, without one the caller's order
 // stands.
-static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
-                     FoldWorkspace* ws, bool ordered, void* stream) {
+static int fold_impl(dcasgd_t h, const void* const* grads, int J, int J_total, float eta_hat,
+                     FoldWorkspace* ws, bool ordered, const float* kept, void* stream) {
     if (!h) return DCASGD_EINVAL;
     if (!h->ready) return fail(h, DCASGD_ESTATE);
-    if (!grads || J < 1 || J > DCASGD_MAX_K || !std::isfinite(eta_hat))
+    if (!grads || J < 1 || J > DCASGD_MAX_K || J_total < J || !std::isfinite(eta_hat))
         return fail(h, DCASGD_EINVAL);
+    if (kept) {
+        // the kept w_t may be a backup row (a pull is the natural way to keep it), but
+        // nothing the fold writes and none of its gradients
+        if (h->bak_bf16 && overlaps(kept, h->d * 4, h->bak, bak_bytes(h))) return fail(h, DCASGD_EINVAL);
+        if (!aligned(kept, 16)) return fail(h, DCASGD_EALIGN);
+        if (overlaps(kept, h->d * 4, h->w, h->d * 4) ||
+            (h->ms && overlaps(kept, h->d * 4, h->ms, h->d * 4)) ||
+            (h->hp.vel && overlaps(kept, h->d * 4, h->hp.vel, h->d * 4)))
+            return fail(h, DCASGD_EINVAL);
+        for (int j = 0; j < J; ++j)
+            if (grads[j] && overlaps(kept, h->d * 4, grads[j], grad_bytes(h)))
+                return fail(h, DCASGD_EINVAL);
+    }
     FoldArgs a{};
     a.J = J;
     for (int j = 0; j < J; ++j) {
@@ -450,7 +463,7 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
             if (overlaps(ws, wb, grads[j], grad_bytes(h))) return fail(h, DCASGD_EINVAL);
     }
     Hyper hp = h->hp;
-    hp.eta = eta_hat / (float)J;            // per-gradient step, formed once in binary32
+    hp.eta = eta_hat / (float)J_total;      // per-gradient step, formed once in binary32
     const size_t n4 = h->d / 4;
     const int threads = h->batch_threads;
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
@@ -482,12 +495,21 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
+          if (kept) {
+            DCASGD_LAUNCH(h, (sync_fold_kernel<decltype(AD)::value, decltype(MO)::value,
+                                               decltype(BF)::value, DCASGD_FOLD_KC,
+                                               decltype(NT)::value, false, true>),
+                          grid, threads, s, hp, h->w, h->ms, a,
+                          static_cast<const FoldWorkspace*>(nullptr), kept, n4, h->d);
+            return;
+          }
           with_bool(ordered, [&](auto OR) {
             DCASGD_LAUNCH(h, (sync_fold_kernel<decltype(AD)::value, decltype(MO)::value,
                                                decltype(BF)::value, DCASGD_FOLD_KC,
-                                               decltype(NT)::value, decltype(OR)::value>),
+                                               decltype(NT)::value, decltype(OR)::value, false>),
                           grid, threads, s, hp, h->w, h->ms, a,
-                          static_cast<const FoldWorkspace*>(ws), n4, h->d);
+                          static_cast<const FoldWorkspace*>(ws),
+                          static_cast<const float*>(nullptr), n4, h->d);
           });
         });
       });
@@ -500,13 +522,20 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, float eta_hat,
 }
 
 int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream) {
-    return fold_impl(h, grads, J, eta_hat, nullptr, false, stream);
+    return fold_impl(h, grads, J, J, eta_hat, nullptr, false, nullptr, stream);
+}
+
+int dcasgd_sync_fold_part(dcasgd_t h, const void* const* grads, int J, int J_total, float eta_hat,
+                          const float* kept_w, void* stream) {
+    if (h && !kept_w) return fail(h, DCASGD_EINVAL);
+    return fold_impl(h, grads, J, J_total, eta_hat, nullptr, false, kept_w, stream);
 }
 
 int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float eta_hat,
                              void* workspace, void* stream) {
     static_assert(sizeof(FoldWorkspace) == DCASGD_FOLD_WS_BYTES, "header and kernels agree");
-    return fold_impl(h, grads, J, eta_hat, static_cast<FoldWorkspace*>(workspace), true, stream);
+    return fold_impl(h, grads, J, J, eta_hat, static_cast<FoldWorkspace*>(workspace), true, nullptr,
+                     stream);
 }
 
 const float* dcasgd_pull(dcasgd_t h, int worker) {

@@ -464,13 +464,16 @@ static_assert(sizeof(FoldWorkspace) == 512 + 16 * FOLD_WS_BLOCKS * 8, "documente
 
 // gp: the J gradient pointers in fold order, either the launch arguments
 // themselves or the list the ordering kernel left in device memory.
-template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool CHECKED>
+// kept: w_t of a fold that is delivered in parts (the caller's copy), or nullptr
+// when the fold starts here and w_t is simply the value of w on entry.
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool ANCH, bool CHECKED>
 __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w,
                                           float* __restrict__ ms, const void* const* gp, int J,
-                                          size_t q, size_t n4) {
+                                          const float* __restrict__ kept, size_t q, size_t n4) {
     if (CHECKED && q >= n4) return;
-    const f32x4 anchor = load4<false>(w, q);
-    f32x4 W = anchor;
+    f32x4 W = load4<false>(w, q);
+    f32x4 anchor = W;
+    if constexpr (ANCH) anchor = load4<NT>(kept, q);
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
     f32x4 V = load_vel4<MOM>(hp, q);
@@ -491,25 +494,27 @@ __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w
     store_vel4<MOM>(hp, q, V);
 }
 
-template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool ORD>
+template <bool ADAPTIVE, bool MOM, bool BF16, int KC, bool NT, bool ORD, bool ANCH>
 __global__ void __launch_bounds__(256)
 sync_fold_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, FoldArgs a,
-                 const FoldWorkspace* __restrict__ ws, size_t n4, size_t d) {
+                 const FoldWorkspace* __restrict__ ws, const float* __restrict__ kept, size_t n4,
+                 size_t d) {
     const void* const* gp = a.grad;
     if constexpr (ORD) gp = ws->ordered;
     const size_t ntiles = (n4 + blockDim.x - 1) / blockDim.x;
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const size_t q = tile * blockDim.x + threadIdx.x;
         if ((tile + 1) * blockDim.x <= n4)
-            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, false>(hp, w, ms, gp, a.J, q, n4);
+            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, ANCH, false>(hp, w, ms, gp, a.J, kept, q, n4);
         else
-            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, true>(hp, w, ms, gp, a.J, q, n4);
+            fold_quad<ADAPTIVE, MOM, BF16, KC, NT, ANCH, true>(hp, w, ms, gp, a.J, kept, q, n4);
     }
     if (blockIdx.x == 0) {
         const size_t i = 4 * n4 + threadIdx.x;
         if (i < d) {
-            const float anchor = w[i];
-            float wi = anchor;
+            float wi = w[i];
+            float anchor = wi;
+            if constexpr (ANCH) anchor = kept[i];
             float si = 0.f;
             if constexpr (ADAPTIVE) si = ms[i];
             float vi = load_vel1<MOM>(hp, i);

@@ -96,3 +96,70 @@ def test_fold_rejects_bad_arguments():
     assert lib.dcasgd_sync_fold(sv._h, bad, 2, 0.1, s) == B.EALIGN
     torch.cuda.synchronize()
     assert sv.t == 0 and float(sv.w.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_fold_delivered_in_parts(mode, bf16):
+    """Forty same-snapshot gradients in parts of 16, 16 and 8 against the kept w_t (a backup
+    row refreshed by a pull, or a plain copy) must leave the bits of the oracle's one fold."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    rng = np.random.default_rng(23)
+    lam0 = 2.0 if mode == W.MODE_A else 0.04
+    J = 40
+    for d in (1, 6, 1027, 70001):
+        for keep_in_row in (True, False):
+            say("fold in parts d=%d mode=%d bf16=%s row=%s" % (d, mode, bf16, keep_in_row))
+            w0 = rng.standard_normal(d).astype(np.float32)
+            g = (0.3 * rng.standard_normal((J, d))).astype(np.float32)
+            if bf16:
+                gt = torch.from_numpy(g).to(torch.bfloat16)
+                g = gt.float().numpy()
+                dev = [gt[j].contiguous().cuda() for j in range(J)]
+            else:
+                dev = [torch.from_numpy(g[j]).cuda() for j in range(J)]
+            sv = B.Server(torch.from_numpy(w0).cuda(), 2, 0.1, lam0, mode, 0.95, 1e-7, grad_bf16=bf16)
+            ref = oracle.Server(w0, 2, 0.1, lam0, mode, 0.95, 1e-7)
+            first = (0.2 * rng.standard_normal(d)).astype(np.float32)    # so that w_t is not w_0
+            first_dev = torch.from_numpy(first).to(sv.grad_dtype).cuda()
+            sv.push(0, first_dev)
+            ref.push(0, first_dev.float().cpu().numpy())
+            kept = sv.pull(1) if keep_in_row else sv.w.clone()
+            if keep_in_row:
+                ref.pull(1)
+            for lo, hi in ((0, 16), (16, 32), (32, 40)):
+                sv.sync_fold_part(dev[lo:hi], J, 2.0, kept)
+            ref.sync_fold(g, 2.0)
+            torch.cuda.synchronize()
+            assert sv.t == ref.t == 1 + J
+            assert_same_bits(sv.w.cpu().numpy(), ref.w(), "fold in parts w d=%d" % d)
+            if mode == W.MODE_A:
+                assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "fold in parts ms d=%d" % d)
+            assert_same_bits(sv.bak[1, :d].cpu().numpy(), ref.bak(1), "the kept row is not written")
+
+
+def test_fold_part_rejects_bad_arguments():
+    import ctypes as C
+    import torch
+    from paper_1609_08326_amd import binding as B
+    lib = B.load()
+    d = 4096
+    sv = B.Server(torch.zeros(d, device="cuda"), 2, 0.1, 2.0, B.MODE_A, 0.9, 1e-7)
+    g = torch.ones(d, device="cuda")
+    kept = torch.zeros(d, device="cuda")
+    ga = (C.c_void_p * 1)(g.data_ptr())
+    s = int(torch.cuda.current_stream().cuda_stream)
+    assert lib.dcasgd_sync_fold_part(sv._h, ga, 1, 4, 0.1, None, s) == B.EINVAL
+    assert lib.dcasgd_sync_fold_part(sv._h, ga, 2, 1, 0.1, kept.data_ptr(), s) == B.EINVAL   # J_total < J
+    assert lib.dcasgd_sync_fold_part(sv._h, ga, 1, 4, 0.1, sv.w.data_ptr(), s) == B.EINVAL
+    assert lib.dcasgd_sync_fold_part(sv._h, ga, 1, 4, 0.1, sv.ms.data_ptr(), s) == B.EINVAL
+    assert lib.dcasgd_sync_fold_part(sv._h, ga, 1, 4, 0.1, g.data_ptr(), s) == B.EINVAL
+    assert lib.dcasgd_sync_fold_part(sv._h, ga, 1, 4, 0.1, kept.data_ptr() + 4, s) == B.EALIGN
+    torch.cuda.synchronize()
+    assert sv.t == 0 and float(sv.w.abs().max()) == 0.0
+    sv16 = B.Server(torch.zeros(d, device="cuda"), 2, 0.1, 2.0, B.MODE_A, 0.9, 1e-7, bak_bf16=True)
+    assert lib.dcasgd_sync_fold_part(sv16._h, ga, 1, 4, 0.1, sv16.bak.data_ptr(), s) == B.EINVAL
+    assert lib.dcasgd_sync_fold_part(sv._h, ga, 1, 4, 0.1, kept.data_ptr(), s) == B.OK
+    torch.cuda.synchronize()
+    assert sv.t == 1
