@@ -76,8 +76,8 @@ def test_random_call_sequence(seed):
         return gt.float().numpy(), [gt[j].contiguous().cuda() for j in range(n)]
 
     ops = ["push", "batch", "batch_repeat", "pull", "fold", "fold_ranked", "push_synth",
-           "worker_then_push", "eta", "momentum", "lambda"]
-    weights = np.array([4, 2, 1, 2, 1, 1, 2, 1, 1, 1, 1], dtype=float)
+           "worker_then_push", "eta", "momentum", "lambda", "fold_parts"]
+    weights = np.array([4, 2, 1, 2, 1, 1, 2, 1, 1, 1, 1, 1], dtype=float)
     trace = []
     for step in range(90):
         op = str(rng.choice(ops, p=weights / weights.sum()))
@@ -119,6 +119,14 @@ def test_random_call_sequence(seed):
                 want = np.argsort(oracle.grad_sqnorms(g), kind="stable")
                 assert perm.tolist() == want.tolist(), (step, perm, want)
                 ref.sync_fold(g[want], eta_hat)
+        elif op == "fold_parts":
+            J = int(rng.integers(17, 41))
+            g, dev = gradients(J)
+            eta_hat = float(np.float32(0.02 * J))
+            kept = sv.w.clone()
+            for lo in range(0, J, 16):
+                sv.sync_fold_part(dev[lo:lo + 16], J, eta_hat, kept)
+            ref.sync_fold(g, eta_hat)
         elif op == "push_synth":
             if not fused_pull:
                 continue                      # the fused launch always refreshes the backup
