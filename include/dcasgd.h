@@ -149,6 +149,15 @@ int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float 
                              void* workspace, void* stream);
 
 /*
+ * Only the first two launches of dcasgd_sync_fold_ordered: the squared norms of
+ * J gradients and their ranking are left in the workspace (same layout), the
+ * model is not touched and t does not advance.  For callers that rank more
+ * gradients than one fold call takes and deliver them with dcasgd_sync_fold_part.
+ */
+int dcasgd_grad_sqnorms(dcasgd_t h, const void* const* grads, int J, void* workspace,
+                        void* stream);
+
+/*
  * The same fold delivered in parts, for more same-snapshot gradients than one
  * call takes (large mini-batch SSGD runs on many workers): J of the J_total
  * gradients are applied with the step eta_hat/J_total and compensated against

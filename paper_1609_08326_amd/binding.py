@@ -36,6 +36,8 @@ _PROTOTYPES = {
                                     C.c_int, C.c_void_p]),
     "dcasgd_sync_fold": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
                                    C.c_void_p]),
+    "dcasgd_grad_sqnorms": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_void_p,
+                                      C.c_void_p]),
     "dcasgd_sync_fold_part": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_int,
                                         C.c_float, C.c_void_p, C.c_void_p]),
     "dcasgd_sync_fold_ordered": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
@@ -292,6 +294,17 @@ class Server:
         _check(load().dcasgd_sync_fold_ordered(self._h, ga, J, float(eta_hat),
                                                workspace.data_ptr(), _stream_ptr(stream)),
                "dcasgd_sync_fold_ordered")
+
+    def grad_sqnorms(self, grads: Sequence, workspace, stream=None) -> None:
+        """Squared norms and ranking of up to 16 gradients into ``workspace`` (read them
+        with fold_order after synchronising); the model is not touched."""
+        J = len(grads)
+        for g in grads:
+            assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
+        assert workspace.is_cuda and workspace.numel() * workspace.element_size() >= FOLD_WS_BYTES
+        ga = (C.c_void_p * J)(*[g.data_ptr() for g in grads])
+        _check(load().dcasgd_grad_sqnorms(self._h, ga, J, workspace.data_ptr(),
+                                          _stream_ptr(stream)), "dcasgd_grad_sqnorms")
 
     def sync_fold_part(self, grads: Sequence, J_total: int, eta_hat: float, kept_w,
                        stream=None) -> None:

@@ -425,7 +425,8 @@ int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdia
 // norm on the device and folded in that order, without one the caller's order
 // stands.
 static int fold_impl(dcasgd_t h, const void* const* grads, int J, int J_total, float eta_hat,
-                     FoldWorkspace* ws, bool ordered, const float* kept, void* stream) {
+                     FoldWorkspace* ws, bool ordered, const float* kept, void* stream,
+                     bool apply = true) {
     if (!h) return DCASGD_EINVAL;
     if (!h->ready) return fail(h, DCASGD_ESTATE);
     if (!grads || J < 1 || J > DCASGD_MAX_K || J_total < J || !std::isfinite(eta_hat))
@@ -490,6 +491,10 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, int J_total, f
           });
         });
         DCASGD_LAUNCH(h, fold_order_kernel, 1, 1024, s, a, ws, (int)nblocks);
+        if (!apply) {                      // norms and ranking only: the model is not touched
+            h->stream = s;
+            return launched(h);
+        }
     }
     with_bool(h->adaptive, [&](auto AD) {
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
@@ -523,6 +528,12 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, int J_total, f
 
 int dcasgd_sync_fold(dcasgd_t h, const void* const* grads, int J, float eta_hat, void* stream) {
     return fold_impl(h, grads, J, J, eta_hat, nullptr, false, nullptr, stream);
+}
+
+int dcasgd_grad_sqnorms(dcasgd_t h, const void* const* grads, int J, void* workspace,
+                        void* stream) {
+    return fold_impl(h, grads, J, J, 0.0f, static_cast<FoldWorkspace*>(workspace), true, nullptr,
+                     stream, false);
 }
 
 int dcasgd_sync_fold_part(dcasgd_t h, const void* const* grads, int J, int J_total, float eta_hat,

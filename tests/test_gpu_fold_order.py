@@ -250,3 +250,41 @@ def test_ordered_fold_replays_from_a_captured_graph():
         assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "replay %d ms" % r)
         other.add_(1.0)
         torch.cuda.synchronize()
+
+
+def test_ranking_forty_gradients_and_folding_them_in_parts():
+    """More gradients than one call takes: norms chunk by chunk (the model untouched),
+    one ranking on the host, then the fold in parts in that order; norms within the bound,
+    order and model equal to the oracle's."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    rng = np.random.default_rng(47)
+    d, J = 50003, 40
+    w0 = rng.standard_normal(d).astype(np.float32)
+    scale = (rng.permutation(J).astype(np.float32)[:, None] * 0.02 + 0.05)
+    g = (scale * rng.standard_normal((J, d))).astype(np.float32)
+    _, dev = device_rows(g, False)
+    sv = B.Server(torch.from_numpy(w0).cuda(), 1, 0.1, 2.0, W.MODE_A, 0.95, 1e-7)
+    ws = B.Server.fold_workspace()
+    sq = []
+    for lo in range(0, J, 16):
+        sv.grad_sqnorms(dev[lo:lo + 16], ws)
+        torch.cuda.synchronize()
+        sq.append(B.Server.fold_order(ws, len(dev[lo:lo + 16]))[0])
+    sq = np.concatenate(sq)
+    assert sv.t == 0
+    assert_same_bits(sv.w.cpu().numpy(), w0, "norms leave the model alone")
+    want = oracle.grad_sqnorms(g)
+    assert np.all(np.abs(sq - want) <= norm_tolerance(d) * want)
+    order = np.argsort(sq, kind="stable")
+    assert order.tolist() == np.argsort(want, kind="stable").tolist()
+    kept = sv.w.clone()
+    ranked = [dev[int(j)] for j in order]
+    for lo in range(0, J, 16):
+        sv.sync_fold_part(ranked[lo:lo + 16], J, 2.0, kept)
+    torch.cuda.synchronize()
+    ref = oracle.Server(w0, 1, 0.1, 2.0, W.MODE_A, 0.95, 1e-7)
+    ref.sync_fold(g[order], 2.0)
+    assert sv.t == ref.t == J
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "ranked fold of forty, w")
+    assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "ranked fold of forty, ms")
