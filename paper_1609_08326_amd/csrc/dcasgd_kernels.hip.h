@@ -210,6 +210,23 @@ __device__ __forceinline__ bool in_midrange(float x) {
     return (u - 0x1F800000u) < 0x40000000u && (u & 0x00FFFFFFu) != 0x007FFFFFu;
 }
 
+// in_midrange for four radicands at once, with the four answers folded by
+// integer max/min instead of four compares each: all ranges hold iff the
+// largest offset is below the span, and a significand pattern is hit iff the
+// smallest difference from it is zero.
+__device__ __forceinline__ bool quad_in_midrange(const float (&x)[4]) {
+    uint32_t off[4], dif[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t u = __float_as_uint(x[c]);
+        off[c] = u - 0x1F800000u;
+        dif[c] = (u & 0x00FFFFFFu) ^ 0x007FFFFFu;
+    }
+    const uint32_t far = max(max(off[0], off[1]), max(off[2], off[3]));
+    const uint32_t near = min(min(dif[0], dif[1]), min(dif[2], dif[3]));
+    return far < 0x40000000u && near != 0u;
+}
+
 // Four parameters at once.  The adaptive lambda needs sqrt and a divide per
 // parameter; when every lane of the wave has all four radicands in the middle
 // of the exponent range (any realistic MeanSquare + eps) the short forms above
@@ -227,7 +244,6 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
         }
     } else {
         float gsq[4], under[4], lam[4];
-        bool mid = hp.lambda_midrange != 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             gsq[c] = g[c] * g[c];
@@ -235,8 +251,8 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
             const float add = hp.one_minus_m * gsq[c];
             ms[c] = keep + add;
             under[c] = ms[c] + hp.eps;
-            mid = mid && in_midrange(under[c]);
         }
+        const bool mid = hp.lambda_midrange != 0 && quad_in_midrange(under);
         if (__builtin_amdgcn_ballot_w64(!mid) == 0) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {

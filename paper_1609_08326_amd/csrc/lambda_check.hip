@@ -10,6 +10,10 @@
 //                                      k = FIRST .. FIRST+COUNT-1  (COUNT <= 2^23)
 //   lambda_check sampled N SEED        N random (radicand, numerator) pairs over
 //                                      the whole admitted range, both signs
+//   lambda_check predicate N SEED      N random groups of four radicands (edges of
+//                                      the window and the excluded pattern included):
+//                                      the four-at-once admission test against
+//                                      four single ones
 // Prints the number of cases and of mismatches, the first few mismatches, and
 // exits non-zero if there is any.
 #include <hip/hip_runtime.h>
@@ -93,6 +97,27 @@ __global__ void check_sampled(unsigned long long n, uint32_t seed, Report* rep) 
     }
 }
 
+// the four-at-once form of the admission test against four single tests
+__global__ void check_predicate(unsigned long long n, uint32_t seed, Report* rep) {
+    for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (unsigned long long)gridDim.x * blockDim.x) {
+        float x[4];
+        bool each = true;
+        uint32_t u = mix((uint32_t)i ^ seed) + (uint32_t)(i >> 32);
+        for (int c = 0; c < 4; ++c) {
+            u = mix(u + 0x9E3779B9u);
+            uint32_t b = u;
+            // steer a share of the draws onto the interesting values
+            if ((u & 0x300u) == 0x100u) b = (b & 0xFF000000u) | 0x007FFFFFu;           // the pattern
+            if ((u & 0x300u) == 0x200u) b = 0x1F800000u + (b & 3u) - 2u;                // lower edge
+            if ((u & 0x300u) == 0x300u) b = 0x5F800000u + (b & 3u) - 2u;                // upper edge
+            x[c] = __uint_as_float(b);
+            each = each && in_midrange(x[c]);
+        }
+        if (quad_in_midrange(x) != each) note(rep, __float_as_uint(x[0]), __float_as_uint(x[1]), 0.f, 0.f);
+    }
+}
+
 static int finish(const char* what, unsigned long long cases, Report* dev) {
     Report host;
     CHECK(hipDeviceSynchronize());
@@ -150,6 +175,13 @@ int main(int argc, char** argv) {
         hipLaunchKernelGGL(check_sampled, dim3(8192), dim3(256), 0, 0, n, seed, rep);
         CHECK(hipGetLastError());
         return finish("sampled", n, rep);
+    }
+    if (!std::strcmp(argv[1], "predicate") && argc >= 4) {
+        const unsigned long long n = std::strtoull(argv[2], nullptr, 0);
+        const uint32_t seed = (uint32_t)std::strtoull(argv[3], nullptr, 0);
+        hipLaunchKernelGGL(check_predicate, dim3(8192), dim3(256), 0, 0, n, seed, rep);
+        CHECK(hipGetLastError());
+        return finish("predicate", n, rep);
     }
     std::fprintf(stderr, "usage: see the header of lambda_check.hip\n");
     return 2;

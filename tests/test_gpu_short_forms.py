@@ -43,3 +43,8 @@ def test_root_and_quotient_on_random_pairs_over_the_whole_range():
 def test_quotient_on_all_radicand_significands_for_a_slice_of_numerators(first):
     out = run("quotients", first, 4096)
     assert "68719476736 cases" in out and " 0 mismatches" in out
+
+
+def test_admission_test_for_four_radicands_equals_four_single_tests():
+    out = run("predicate", 1 << 32, 77)
+    assert " 0 mismatches" in out
