@@ -52,6 +52,13 @@ def lib() -> C.CDLL:
         L.oracle_philox4x32_10.restype = None
         L.oracle_normal_pair.argtypes = [C.c_uint32, C.c_uint32, f32p]
         L.oracle_normal_pair.restype = None
+        L.oracle_philox4x32_10_many.argtypes = [u32p, u32p, u32p, C.c_size_t]
+        L.oracle_philox4x32_10_many.restype = None
+        L.oracle_normal_pairs.argtypes = [u32p, u32p, f32p, C.c_size_t]
+        L.oracle_normal_pairs.restype = None
+        L.oracle_run_checked.argtypes = [vp, i32p, C.c_size_t, f32p, f32p, C.c_float, C.c_uint64,
+                                         u64p, C.c_int, C.c_int, C.POINTER(C.c_longlong)]
+        L.oracle_run_checked.restype = C.c_int
         L.oracle_normal_quad.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, f32p]
         L.oracle_normal_quad.restype = None
         L.oracle_bf16_rne.argtypes = [f32p, C.POINTER(C.c_uint16), C.c_size_t]
@@ -117,6 +124,29 @@ def philox4x32_10(ctr, key) -> np.ndarray:
     lib().oracle_philox4x32_10(c.ctypes.data_as(u32p), k.ctypes.data_as(u32p),
                                out.ctypes.data_as(u32p))
     return out
+
+
+def philox4x32_10_many(ctr, key) -> np.ndarray:
+    """Philox4x32-10 of n counters (n x 4 words) under n keys (n x 2 words): n x 4 words."""
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.ndim == 2 and c.shape[1] == 4 and k.shape == (c.shape[0], 2)
+    out = np.zeros_like(c)
+    u32p = C.POINTER(C.c_uint32)
+    lib().oracle_philox4x32_10_many(c.ctypes.data_as(u32p), k.ctypes.data_as(u32p),
+                                    out.ctypes.data_as(u32p), c.shape[0])
+    return out
+
+
+def normal_pairs(xa, xb) -> np.ndarray:
+    """normal_pair over arrays of words: n x 2 float32."""
+    a = np.ascontiguousarray(xa, dtype=np.uint32)
+    b = np.ascontiguousarray(xb, dtype=np.uint32)
+    assert a.ndim == 1 and a.shape == b.shape
+    z = np.zeros((a.size, 2), dtype=np.float32)
+    u32p = C.POINTER(C.c_uint32)
+    lib().oracle_normal_pairs(a.ctypes.data_as(u32p), b.ctypes.data_as(u32p), _fp(z), a.size)
+    return z
 
 
 def normal_pair(xa: int, xb: int) -> np.ndarray:
@@ -254,8 +284,12 @@ class Server:
             raise ValueError("bad worker id")
         return out
 
-    def run(self, order, hdiag, wstar, sigma, seed, gidx=None, as_bf16=False, nthreads=1) -> None:
-        """T arrivals: gradient at the worker's backup, push, pull (Algorithm 1's cycle)."""
+    def run(self, order, hdiag, wstar, sigma, seed, gidx=None, as_bf16=False, nthreads=1,
+            check_finite=False):
+        """T arrivals: gradient at the worker's backup, push, pull (Algorithm 1's cycle).
+        With check_finite the state is inspected after every push and the index of the
+        first arrival that left an inf or NaN in w, MeanSquare or the velocity is returned
+        (None if there was none)."""
         order = np.ascontiguousarray(order, dtype=np.int32)
         hdiag, wstar = _f32(hdiag), _f32(wstar)
         assert hdiag.size == self.n and wstar.size == self.n
@@ -264,8 +298,18 @@ class Server:
             gidx = np.ascontiguousarray(gidx, dtype=np.uint64)
             assert gidx.size == self.n
             gp = gidx.ctypes.data_as(C.POINTER(C.c_uint64))
+        if check_finite:
+            bad = C.c_longlong(-1)
+            rc = lib().oracle_run_checked(self._h, order.ctypes.data_as(C.POINTER(C.c_int)),
+                                          order.size, _fp(hdiag), _fp(wstar), float(sigma),
+                                          int(seed), gp, int(bool(as_bf16)), int(nthreads),
+                                          C.byref(bad))
+            if rc != 0:
+                raise ValueError("order holds a worker id outside [0, M)")
+            return None if bad.value < 0 else int(bad.value)
         rc = lib().oracle_run(self._h, order.ctypes.data_as(C.POINTER(C.c_int)), order.size,
                               _fp(hdiag), _fp(wstar), float(sigma), int(seed), gp,
                               int(bool(as_bf16)), int(nthreads))
         if rc != 0:
             raise ValueError("order holds a worker id outside [0, M)")
+        return None

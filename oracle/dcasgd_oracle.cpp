@@ -310,6 +310,33 @@ void run_range(Server& sv, const int* order, size_t T, uint64_t t0,
     }
 }
 
+// The same sequence with a look at the state after every push: returns the
+// index of the first event after whose push some w, MeanSquare or velocity
+// value of [lo, hi) is not finite, or T if there is none.  (A non-finite
+// backup can only come from a non-finite w.)  No arithmetic of its own.
+size_t run_range_checked(Server& sv, const int* order, size_t T, uint64_t t0,
+                         const float* hdiag, const float* wstar, float sigma, uint64_t seed,
+                         const uint64_t* gidx, int as_bf16, float* gbuf, size_t lo, size_t hi) {
+    size_t first_bad = T;
+    for (size_t e = 0; e < T; ++e) {
+        const int m = order[e];
+        synth_grad_range(sv.bak[m].data(), hdiag, wstar, sigma, seed,
+                         (uint32_t)(t0 + e), gidx, as_bf16, gbuf, lo, hi);
+        push_range(sv, m, gbuf, lo, hi);
+        if (first_bad == T) {
+            bool finite = true;
+            for (size_t i = lo; i < hi && finite; ++i) {
+                finite = std::isfinite(sv.w[i]);
+                if (finite && !sv.ms.empty()) finite = std::isfinite(sv.ms[i]);
+                if (finite && !sv.vel.empty()) finite = std::isfinite(sv.vel[i]);
+            }
+            if (!finite) first_bad = e;
+        }
+        pull_range(sv, m, lo, hi);
+    }
+    return first_bad;
+}
+
 // Denormals must be kept: clear flush-to-zero / denormals-are-zero for the
 // duration of a call in case the embedding process switched them on.
 struct KeepDenormals {
@@ -334,6 +361,17 @@ void oracle_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* ou
 void oracle_normal_pair(uint32_t xa, uint32_t xb, float* z) {
     KeepDenormals guard;
     normal_pair(xa, xb, &z[0], &z[1]);
+}
+
+// The same two calls over arrays (n counters with their keys; n word pairs):
+// plain loops, so that tests can compare millions of cases.
+void oracle_philox4x32_10_many(const uint32_t* ctr, const uint32_t* key, uint32_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) philox4x32_10(ctr + 4 * i, key + 2 * i, out + 4 * i);
+}
+
+void oracle_normal_pairs(const uint32_t* xa, const uint32_t* xb, float* z, size_t n) {
+    KeepDenormals guard;
+    for (size_t i = 0; i < n; ++i) normal_pair(xa[i], xb[i], &z[2 * i], &z[2 * i + 1]);
 }
 
 void oracle_normal_quad(uint64_t seed, uint32_t t, uint32_t q, uint32_t tag, float* z) {
@@ -518,6 +556,39 @@ int oracle_run(void* h, const int* order, size_t T, const float* hdiag,
         }
         for (auto& th : pool) th.join();
     }
+    sv.t += T;
+    return 0;
+}
+
+// oracle_run that also reports when the state stopped being finite: *first_bad
+// receives the index of the first arrival after whose push some element of w,
+// MeanSquare or the velocity is inf or NaN, or -1 if every state stayed finite.
+int oracle_run_checked(void* h, const int* order, size_t T, const float* hdiag,
+                       const float* wstar, float sigma, uint64_t seed,
+                       const uint64_t* gidx, int as_bf16, int nthreads, long long* first_bad) {
+    Server& sv = *static_cast<Server*>(h);
+    for (size_t e = 0; e < T; ++e)
+        if (order[e] < 0 || order[e] >= sv.M) return -1;
+    if (nthreads < 1) nthreads = 1;
+    std::vector<float> gbuf(sv.n);
+    std::vector<size_t> bad((size_t)nthreads, T);
+    const uint64_t t0 = sv.t;
+    const size_t chunk = (sv.n + nthreads - 1) / nthreads;
+    std::vector<std::thread> pool;
+    for (int k = 0; k < nthreads; ++k) {
+        const size_t lo = (size_t)k * chunk;
+        const size_t hi = lo + chunk < sv.n ? lo + chunk : sv.n;
+        if (lo >= hi) continue;
+        pool.emplace_back([&, k, lo, hi] {
+            KeepDenormals guard;
+            bad[(size_t)k] = run_range_checked(sv, order, T, t0, hdiag, wstar, sigma, seed, gidx,
+                                               as_bf16, gbuf.data(), lo, hi);
+        });
+    }
+    for (auto& th : pool) th.join();
+    size_t first = T;
+    for (size_t b : bad) first = b < first ? b : first;
+    *first_bad = first == T ? -1 : (long long)first;
     sv.t += T;
     return 0;
 }

@@ -97,8 +97,9 @@ def oracle_run(wl: W.Workload, hdiag, wstar, arrivals, idx=None, nthreads: int =
         sv.set_momentum(momentum)
     if bak_bf16:
         sv.set_backup_bf16()
-    sv.run(arrivals, hdiag, wstar, wl.sigma, wl.seed, gidx=idx, as_bf16=wl.grad_bf16,
-           nthreads=nthreads)
+    bad = sv.run(arrivals, hdiag, wstar, wl.sigma, wl.seed, gidx=idx, as_bf16=wl.grad_bf16,
+                 nthreads=nthreads, check_finite=True)
+    assert bad is None, "%s: oracle state not finite after push %d" % (wl.name, bad)
     return sv
 
 

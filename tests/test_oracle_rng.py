@@ -41,6 +41,27 @@ def test_philox_known_answers():
         assert [int(x) for x in got_py] == v[6:10]
 
 
+def test_philox_matches_second_implementation_on_a_million_counters():
+    rng = np.random.default_rng(70)
+    n = 1 << 20
+    ctr = rng.integers(0, 1 << 32, size=(n, 4), dtype=np.uint64)
+    key = rng.integers(0, 1 << 32, size=(n, 2), dtype=np.uint64)
+    # a quarter of them shaped like the gradient noise's counters: (i/4, t, 0, 0), one key
+    k = n // 4
+    ctr[:k, 0] = np.arange(k) * 97 % (1 << 26)
+    ctr[:k, 1] = np.arange(k) % 4000
+    ctr[:k, 2:] = 0
+    key[:k] = [160908326 + 2, 0]
+    # and the corners of the word range
+    ctr[k:k + 4] = [[0, 0, 0, 0], [0xFFFFFFFF] * 4, [0, 0xFFFFFFFF, 0, 0xFFFFFFFF], [1, 0, 0, 0]]
+    key[k:k + 4] = [[0, 0], [0xFFFFFFFF, 0xFFFFFFFF], [0xFFFFFFFF, 0], [0, 1]]
+    got = oracle.philox4x32_10_many(ctr, key)
+    assert np.array_equal(got, philox_py(ctr, key))
+    # the array entry point is the single-counter one in a loop
+    for i in (0, 1, k, k + 1, n - 1):
+        assert np.array_equal(got[i], oracle.philox4x32_10(ctr[i], key[i]))
+
+
 def test_philox_matches_second_implementation():
     rng = np.random.default_rng(7)
     ctr = rng.integers(0, 1 << 32, size=(5000, 4), dtype=np.uint64)
@@ -62,6 +83,114 @@ def box_muller_f64(xa, xb):
     ang = 2.0 * math.pi * (np.asarray(xb, dtype=np.uint64) >> np.uint64(8)).astype(np.float64) / 2.0**24
     r = np.sqrt(-2.0 * np.log(u))
     return r * np.cos(ang), r * np.sin(ang)
+
+
+# --- the noise transform once more, on numpy float32 arrays -----------------------
+# Written from the definition of the transform (not from the oracle's source):
+# every line is one binary32 operation on arrays, which numpy evaluates with
+# one IEEE rounding each, so the result must be the oracle's bits.
+def normal_pairs_np(xa, xb):
+    f = np.float32
+    xa = np.asarray(xa, dtype=np.uint32)
+    xb = np.asarray(xb, dtype=np.uint32)
+    # radius: u = ((xa >> 8) + 1) / 2^24 in (0, 1]
+    k = (xa >> np.uint32(8)) + np.uint32(1)
+    u = k.astype(f) * f(2.0 ** -24)
+    ub = u.view(np.uint32)
+    e = (ub >> np.uint32(23)).astype(np.int32) - 127
+    mt = ((ub & np.uint32(0x007FFFFF)) | np.uint32(0x3F800000)).view(f)
+    big = mt > f(1.41421354)
+    mt = np.where(big, mt * f(0.5), mt)
+    e = np.where(big, e + 1, e)
+    num = mt - f(1.0)
+    den = mt + f(1.0)
+    s = num / den
+    s2 = s * s
+    p = np.full(s.shape, f(0.11111111))
+    p = p * s2
+    p = p + f(0.14285715)
+    p = p * s2
+    p = p + f(0.2)
+    p = p * s2
+    p = p + f(0.33333334)
+    p = p * s2
+    p = p + f(1.0)
+    twos = f(2.0) * s
+    lm = twos * p
+    el = e.astype(f) * f(0.69314718)
+    lnu = el + lm
+    arg = f(-2.0) * lnu
+    r = np.sqrt(arg)
+    # angle 2*pi*j/2^24 folded to [0, pi/4]
+    j = xb >> np.uint32(8)
+    quadrant = j >> np.uint32(22)
+    rr = j & np.uint32(0x3FFFFF)
+    swap = rr > np.uint32(0x200000)
+    rr = np.where(swap, np.uint32(0x400000) - rr, rr)
+    x = rr.astype(f) * f(float.fromhex("0x1.921fb6p-22"))
+    x2 = x * x
+    sp = np.full(x.shape, f(2.7557319e-6))
+    sp = sp * x2
+    sp = sp - f(1.9841270e-4)
+    sp = sp * x2
+    sp = sp + f(8.3333333e-3)
+    sp = sp * x2
+    sp = sp - f(0.16666667)
+    sp = sp * x2
+    sp = sp + f(1.0)
+    sn = x * sp
+    cp = np.full(x.shape, f(-2.7557319e-7))
+    cp = cp * x2
+    cp = cp + f(2.4801587e-5)
+    cp = cp * x2
+    cp = cp - f(1.3888889e-3)
+    cp = cp * x2
+    cp = cp + f(4.1666668e-2)
+    cp = cp * x2
+    cp = cp - f(0.5)
+    cp = cp * x2
+    cs = cp + f(1.0)
+    sn, cs = np.where(swap, cs, sn), np.where(swap, sn, cs)
+    C = np.select([quadrant == 0, quadrant == 1, quadrant == 2], [cs, -sn, -cs], sn)
+    S = np.select([quadrant == 0, quadrant == 1, quadrant == 2], [sn, cs, -sn], -cs)
+    z0 = r * C
+    z1 = r * S
+    assert z0.dtype == f and z1.dtype == f
+    return np.stack([z0, z1], axis=-1)
+
+
+def corner_words():
+    xas = [0x00000000, 0x000000FF, 0x00000100, 0x7FFFFFFF, 0x80000000, 0xB504F300,
+           0xB504F400, 0xB504F200, 0x6A09E600, 0x6A09E700, 0xFFFFFE00, 0xFFFFFF00, 0xFFFFFFFF]
+    js = []
+    for octant in range(8):
+        base = octant * 0x200000
+        js += [base, base + 1, base + 0x1FFFFF, (base + 0x200000) & 0xFFFFFF, base + 0x100000]
+    xa, xb = np.meshgrid(np.array(xas, dtype=np.uint32),
+                         (np.array(js, dtype=np.uint32) << np.uint32(8)) | np.uint32(0x5A))
+    return xa.ravel(), xb.ravel()
+
+
+def test_normal_pair_bit_for_bit_against_numpy_float32():
+    rng = np.random.default_rng(23)
+    n = 1 << 18
+    xa = rng.integers(0, 1 << 32, size=n, dtype=np.uint64).astype(np.uint32)
+    xb = rng.integers(0, 1 << 32, size=n, dtype=np.uint64).astype(np.uint32)
+    # small u (large radius), u near the fold of the mantissa, angles next to octant edges
+    xa[:4096] = rng.integers(0, 1 << 14, size=4096, dtype=np.uint64).astype(np.uint32)
+    xa[4096:8192] = (0xB504F3 + rng.integers(-600, 600, size=4096)).astype(np.uint32) << np.uint32(8)
+    edge = (rng.integers(0, 8, size=8192) * 0x200000 + rng.integers(-40, 40, size=8192)) % (1 << 24)
+    xb[:8192] = edge.astype(np.uint32) << np.uint32(8)
+    ca, cb = corner_words()
+    xa, xb = np.concatenate([xa, ca]), np.concatenate([xb, cb])
+    got = oracle.normal_pairs(xa, xb)
+    want = normal_pairs_np(xa, xb)
+    bad = np.flatnonzero((got.view(np.uint32) != want.view(np.uint32)).any(axis=1))
+    assert bad.size == 0, (bad.size, hex(int(xa[bad[0]])), hex(int(xb[bad[0]])), got[bad[0]], want[bad[0]])
+    # the array entry point is the scalar one in a loop
+    for i in (0, 5000, n - 1, n + 3):
+        assert np.array_equal(oracle.normal_pair(int(xa[i]), int(xb[i])).view(np.uint32),
+                              got[i].view(np.uint32))
 
 
 def test_normal_pair_against_libm_double():
