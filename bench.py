@@ -12,6 +12,12 @@ arrival either way.  Inputs are resident in HBM before the timed region.
 Prints ONE JSON line.  `value` is whole-path element-updates/s; `roofline`
 describes the server-update kernel alone (HIP events around it, inside the
 timed region); `cpu_baseline` times the CPU oracle on a bounded sample.
+
+After the headline region (untouched by what follows) the default run adds:
+a second short leg of the same workload in which the worker kernel leaves
+nothing in the last-level cache, so that `roofline.frac_nothing_cached` is the
+push against HBM alone; and one short leg per other configuration and for the
+synchronous fold, reported under `all_configs`.
 """
 from __future__ import annotations
 
@@ -53,6 +59,17 @@ def read_profile(name: str, key: str = "traffic_bytes_per_launch"):
     path = os.path.join(ROOT, "profiles", "pmc_%s.txt" % name)
     try:
         m = re.search(r"^%s:\s*([0-9.eE+]+)" % key, open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def read_probe(key: str, size: str):
+    """A ceiling the stand-alone memory probe measured (GB/s), from its committed summary:
+    `key` for the vector length `size` ("25m" or "138m")."""
+    path = os.path.join(ROOT, "profiles", "membw_probe_mi355x.txt")
+    try:
+        m = re.search(r"^%s_%s:\s*([0-9.eE+]+)" % (key, size), open(path).read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
@@ -125,57 +142,22 @@ def cpu_baseline(wl, target_s: float, bak_bf16: bool = False):
                          "sample": "%d arrivals, 1 thread, %.1f s" % (T1, dt1)}}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--threads", type=int, default=0)
-    ap.add_argument("--items", type=int, default=0)
-    ap.add_argument("--max-blocks", type=int, default=0)
-    ap.add_argument("--streaming", type=int, default=-1, help="0, 1 or 2 (see dcasgd_set_launch)")
-    ap.add_argument("--synth-threads", type=int, default=0)
-    ap.add_argument("--synth-items", type=int, default=0)
-    ap.add_argument("--fused-worker", action="store_true",
-                    help="also time the worker+push fusion (dcasgd_push_synth) and report it "
-                         "under 'fused_worker_path'; K=1 workloads only")
-    ap.add_argument("--variant", choices=["a", "c"], default=None,
-                    help="override the workload's variant (c: constant lambda 0.04, a: adaptive "
-                         "lambda0 2, m 0.95, eps 1e-7) to time the other kernel at the same size")
-    ap.add_argument("--unfused", action="store_true",
-                    help="K=1 workloads: push and pull as two launches (24 + 8 bytes per update "
-                         "in the adaptive variant) instead of the fused one")
-    ap.add_argument("--graph", type=int, default=0, metavar="G",
-                    help="also capture a block of G arrivals (worker gradient + push each) into a "
-                         "HIP graph and time its replays, reported under 'graph_replay_path'; "
-                         "meant for the launch-bound 1 MB workloads, K=1 only")
-    ap.add_argument("--no-events", action="store_true",
-                    help="no per-kernel events at all (whole-path timing only)")
-    ap.add_argument("--stream-events", action="store_true",
-                    help="additionally record stream events between the kernels of a step and "
-                         "report their intervals (adds a dispatch gap per event)")
-    ap.add_argument("--bak-bf16", action="store_true",
-                    help="snapshots handed out and kept as bfloat16 (a storage variant; the "
-                         "default measures the float32 backups of the configurations)")
-    ap.add_argument("--native-loop", action="store_true",
-                    help="additionally time the same arrivals through dcasgd_run_synth")
-    ap.add_argument("--ordered", action="store_true",
-                    help="fold workload: after the timed region, time the same steps again "
-                         "with the gradients ranked by norm on the device before each fold")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0,
-                    help="CPU oracle sample length; 0 skips the baseline")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by index range, "
-              "one GPU holds one shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
-        return 2
-
+def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: bool = False,
+            arrivals_iid: bool = False, extras: bool = False) -> dict:
+    """Time n_steps steps of one workload (after n_warm untimed ones) and return the report:
+    the keys of the JSON line, `roofline` for the server-update kernel included.
+    uncached_worker: the worker kernel reads its snapshot and writes its gradient
+    non-temporally, so the push finds nothing in the last-level cache.
+    arrivals_iid (queued workloads): the queue is filled by independent uniform arrivals
+    instead of distinct workers; it is then delivered in pieces that hold distinct workers,
+    because a repeated worker's second gradient needs the snapshot its first push leaves.
+    extras: also run the optional paths the command line asks for."""
+    import numpy as np
     import torch
     from paper_1609_08326_amd import binding as B
     from paper_1609_08326_amd import workloads as W
 
-    wl = W.get(args.workload)
+    wl = W.get(workload)
     own_mode = wl.mode
     if args.variant == "c":
         wl = wl.replace(name=wl.name + "+c", mode=W.MODE_C, lambda0=0.04, ema_m=0.0, eps=0.0)
@@ -186,8 +168,10 @@ def main() -> int:
     K = wl.K
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    n_steps, n_warm = args.steps, args.warmup
-    arrivals = wl.replace(T=(n_steps + n_warm) * K).arrivals()
+    order_wl = wl.replace(T=(n_steps + n_warm) * K)
+    if arrivals_iid and batched:
+        order_wl = order_wl.replace(order="iid")
+    arrivals = order_wl.arrivals()
 
     hd = torch.from_numpy(wl.hdiag()).to(dev)
     ws = torch.from_numpy(wl.wstar()).to(dev)
@@ -210,15 +194,39 @@ def main() -> int:
     stream_events = use_events and (args.stream_events or not kernel_events)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_steps)] \
         if stream_events else None
+    pieces_launched = [0]
+
+    def pieces_of(ms_):
+        """Consecutive runs of a queue that hold distinct workers."""
+        start = 0
+        while start < len(ms_):
+            end = start + 1
+            while end < len(ms_) and ms_[end] not in ms_[start:end]:
+                end += 1
+            yield start, end
+            start = end
 
     def step(i: int, rec) -> None:
         base = i * K
         ms_ = [int(m) for m in arrivals[base:base + K]]
         if rec:
             rec[0].record()
+        if batched and arrivals_iid:
+            for start, end in pieces_of(ms_):
+                for j in range(start, end):
+                    B.synth_grad(sv.snapshot(ms_[j]), hd, ws, wl.sigma, wl.seed, base + j, gbuf[j],
+                                 threads=args.synth_threads, items=args.synth_items,
+                                 uncached=uncached_worker)
+                sv.push_batch(ms_[start:end], gbuf[start:end])
+                pieces_launched[0] += 1
+            if rec:
+                rec[1].record()
+                rec[2].record()
+            return
         for j, m in enumerate(ms_):
             B.synth_grad(sv.w if sync else sv.snapshot(m), hd, ws, wl.sigma, wl.seed, base + j,
-                         gbuf[j], threads=args.synth_threads, items=args.synth_items)
+                         gbuf[j], threads=args.synth_threads, items=args.synth_items,
+                         uncached=uncached_worker)
         if rec:
             rec[1].record()
         if sync:
@@ -235,6 +243,7 @@ def main() -> int:
     for i in range(n_warm):
         step(i, None)
     torch.cuda.synchronize()
+    pieces_launched[0] = 0
 
     def timed_region():
         if kernel_events:
@@ -262,6 +271,7 @@ def main() -> int:
         # with stream events around the kernels instead
         kernel_events, stream_events = False, True
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_steps)]
+        pieces_launched[0] = 0
         elapsed, kernel_ms, kernel_launches, kernel_each = timed_region()
 
     updates = wl.d * K * n_steps
@@ -290,6 +300,14 @@ def main() -> int:
         "config": {"workload": wl.name, "d": wl.d, "M": wl.M, "K": K,
                    "variant": "DC-ASGD-a" if wl.mode == 1 else "DC-ASGD-c",
                    "snapshots": "bf16" if args.bak_bf16 else "f32",
+                   "arrivals": ("independent uniform draws; a queue is delivered in pieces of "
+                                "distinct workers" if arrivals_iid and batched else
+                                {"round_robin": "round robin", "iid": "independent uniform draws",
+                                 "queues": "per queue a random choice of K distinct workers (one "
+                                           "gradient in flight per worker, Algorithm 1)",
+                                 "sync": "none (all gradients taken at the current model)"}[wl.order]),
+                   "worker_kernel": ("leaves nothing in the last-level cache" if uncached_worker else
+                                     "leaves its snapshot and gradient cacheable"),
                    "step": ("synth_grad x%d + synchronous fold" if sync else
                             "synth_grad x%d + fused push+pull") % K},
     }
@@ -301,22 +319,34 @@ def main() -> int:
             kernel_launches = n_steps
         launch_bytes = bpu * wl.d * K
         achieved = launch_bytes / (push_ms * 1e-3) / 1e9
+        pname = "%s_%s" % (kname, wl.name.split("_")[0])
         out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": achieved,
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                           "traffic": read_profile("%s_%s" % (kname, wl.name.split("_")[0])),
+                           "traffic": read_profile(pname),
+                           "traffic_source": "profiles/pmc_%s.txt (rocprofv3 FETCH_SIZE and "
+                                             "WRITE_SIZE of this kernel and workload, committed; "
+                                             "not measured in this run)" % pname,
                            "avg_launch_ms": push_ms,
                            "algorithmic_bytes_per_launch": launch_bytes,
                            "bytes_per_element_update": bpu}
-        valu = read_profile("%s_%s" % (kname, wl.name.split("_")[0]), "valu_instr_per_launch")
-        if sync and valu:
-            # the fold moves 5 B per update and is bound by vector issue instead:
-            # measured wavefront VALU instructions per launch x 64 lanes / time
+        valu = read_profile(pname, "valu_instr_per_launch")
+        if valu:
+            # vector issue: measured wavefront VALU instructions per launch x 64 lanes / time
             lane_rate = valu * 64 / (push_ms * 1e-3) / 1e12
+            out["roofline"]["alu_achieved_Tlane_per_s"] = lane_rate
+            out["roofline"]["alu_peak_Tlane_per_s"] = VALU_PEAK_TLANE
+            out["roofline"]["alu_frac"] = lane_rate / VALU_PEAK_TLANE
+            out["roofline"]["valu_instr_per_element_update"] = valu * 64 / (wl.d * K)
+        if sync and valu:
+            # the fold moves 5 B per update and is bound by vector issue instead
+            hbm = out["roofline"]
             out["roofline"] = {"bound": "alu", "kernel": kname, "achieved": lane_rate,
                                "peak": VALU_PEAK_TLANE, "unit": "T lane-instr/s",
                                "frac": lane_rate / VALU_PEAK_TLANE,
-                               "traffic": out["roofline"]["traffic"], "avg_launch_ms": push_ms,
-                               "hbm_achieved_GBs": achieved,
+                               "traffic": hbm["traffic"], "traffic_source": hbm["traffic_source"],
+                               "avg_launch_ms": push_ms,
+                               "hbm_achieved_GBs": achieved, "hbm_frac": achieved / HBM_PEAK_GBS,
+                               "valu_instr_per_element_update": valu * 64 / (wl.d * K),
                                "algorithmic_bytes_per_launch": launch_bytes,
                                "bytes_per_element_update": bpu}
         out["server_update_only"] = {"value": wl.d * K / (push_ms * 1e-3),
@@ -324,13 +354,14 @@ def main() -> int:
         if kernel_events and kernel_each is not None and kernel_each.size >= n_steps \
                 and kernel_each.size % n_steps == 0:
             # spread over the region: server-kernel time of each step (its launches added up)
-            import numpy as np
             per_step = kernel_each.reshape(n_steps, -1).sum(axis=1, dtype="float64")
             p10, p50, p90 = (float(x) for x in np.percentile(per_step, [10, 50, 90]))
             out["roofline"]["launch_ms_p10_median_p90"] = [p10, p50, p90]
         out["roofline"]["launches_timed"] = kernel_launches
         out["roofline"]["timed_by"] = ("HIP events attached to each launch" if kernel_events
                                        else "HIP stream events around each launch")
+        if batched and arrivals_iid:
+            out["roofline"]["launches_per_queue"] = pieces_launched[0] / n_steps
         out["worker_and_gaps_ms_per_step"] = 1e3 * elapsed / n_steps - push_ms
         if stream_events:
             synth_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / n_steps
@@ -339,6 +370,9 @@ def main() -> int:
                 "worker_ms_per_step": synth_ms,
                 "server_ms_per_step": sum(e[1].elapsed_time(e[2]) for e in ev) / n_steps,
                 "worker_achieved_GBs": synth_bytes / (synth_ms * 1e-3) / 1e9}
+    if not extras:
+        out["_wl"] = wl
+        return out
     if args.fused_worker and K == 1:
         # same arrivals, one launch per arrival: the gradient never leaves registers
         torch.cuda.synchronize()
@@ -442,7 +476,159 @@ def main() -> int:
                                     "note": ("worker fused into the push, " if args.fused_worker
                                              else "worker gradient + fused push+pull per arrival, ")
                                             + "launches replayed from one HIP graph"}
-    if args.cpu_seconds > 0 and not sync:
+    out["_wl"] = wl
+    return out
+
+
+def leg_summary(rep: dict) -> dict:
+    """The figures of one extra leg that go under `all_configs`."""
+    r = rep.get("roofline", {})
+    d = {"workload": rep["config"]["workload"], "arrivals": rep["config"]["arrivals"],
+         "steps": rep["steps"], "warmup": rep["warmup"],
+         "value": rep["value"], "unit": rep["unit"], "ms_per_step": rep["ms_per_step"]}
+    if r:
+        d.update({"kernel": r["kernel"], "avg_launch_ms": r["avg_launch_ms"],
+                  "bytes_per_element_update": r["bytes_per_element_update"],
+                  "server_update_only": rep["server_update_only"]["value"],
+                  "timed_by": r["timed_by"]})
+        for k in ("alu_frac", "valu_instr_per_element_update", "launches_per_queue",
+                  "launch_ms_p10_median_p90"):
+            if k in r:
+                d[k] = r[k]
+        if r["bound"] == "alu":
+            d.update({"bound": "alu", "frac": r["frac"], "hbm_frac": r["hbm_frac"],
+                      "hbm_achieved_GBs": r["hbm_achieved_GBs"]})
+        elif rep["config"]["d"] * 4 < (16 << 20):
+            # 1 MB vectors: a launch takes longer to issue than to run; no roofline applies
+            d.update({"bound": "launch latency", "frac": None, "achieved_GBs": r["achieved"]})
+        else:
+            d.update({"bound": "hbm", "frac": r["frac"], "achieved_GBs": r["achieved"]})
+    for k in ("native_loop_path", "fused_worker_path"):
+        if k in rep:
+            d[k] = {"value": rep[k]["value"], "ms_per_step": rep[k]["ms_per_step"]}
+    return d
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--threads", type=int, default=0)
+    ap.add_argument("--items", type=int, default=0)
+    ap.add_argument("--max-blocks", type=int, default=0)
+    ap.add_argument("--streaming", type=int, default=-1, help="0..3 (see dcasgd_set_launch)")
+    ap.add_argument("--synth-threads", type=int, default=0)
+    ap.add_argument("--synth-items", type=int, default=0)
+    ap.add_argument("--fused-worker", action="store_true",
+                    help="also time the worker+push fusion (dcasgd_push_synth) and report it "
+                         "under 'fused_worker_path'; K=1 workloads only")
+    ap.add_argument("--variant", choices=["a", "c"], default=None,
+                    help="override the workload's variant (c: constant lambda 0.04, a: adaptive "
+                         "lambda0 2, m 0.95, eps 1e-7) to time the other kernel at the same size")
+    ap.add_argument("--unfused", action="store_true",
+                    help="K=1 workloads: push and pull as two launches (24 + 8 bytes per update "
+                         "in the adaptive variant) instead of the fused one")
+    ap.add_argument("--graph", type=int, default=0, metavar="G",
+                    help="also capture a block of G arrivals (worker gradient + push each) into a "
+                         "HIP graph and time its replays, reported under 'graph_replay_path'; "
+                         "meant for the launch-bound 1 MB workloads, K=1 only")
+    ap.add_argument("--no-events", action="store_true",
+                    help="no per-kernel events at all (whole-path timing only)")
+    ap.add_argument("--stream-events", action="store_true",
+                    help="additionally record stream events between the kernels of a step and "
+                         "report their intervals (adds a dispatch gap per event)")
+    ap.add_argument("--bak-bf16", action="store_true",
+                    help="snapshots handed out and kept as bfloat16 (a storage variant; the "
+                         "default measures the float32 backups of the configurations)")
+    ap.add_argument("--native-loop", action="store_true",
+                    help="additionally time the same arrivals through dcasgd_run_synth")
+    ap.add_argument("--ordered", action="store_true",
+                    help="fold workload: after the timed region, time the same steps again "
+                         "with the gradients ranked by norm on the device before each fold")
+    ap.add_argument("--uncached-worker", action="store_true",
+                    help="the worker kernel leaves nothing in the last-level cache (the headline "
+                         "leaves its snapshot and gradient cacheable)")
+    ap.add_argument("--iid-queues", action="store_true",
+                    help="queued workload: fill the queues by independent uniform arrivals")
+    ap.add_argument("--legs", default="default",
+                    help="'default': after the headline region also the nothing-cached leg and "
+                         "one leg per other configuration (reported under all_configs) when the "
+                         "workload is the headline one and no variant flag is given; 'none': "
+                         "headline only; or a comma list of cfg0,cfg1,cfg2,cfg3,cfg3iid,cfg4,fold")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="CPU oracle sample length; 0 skips the baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by index range, "
+              "one GPU holds one shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    n_steps, n_warm = args.steps, args.warmup
+    out = measure(args, args.workload, n_steps, n_warm, uncached_worker=args.uncached_worker,
+                  arrivals_iid=args.iid_queues, extras=True)
+    wl = out.pop("_wl")
+
+    plain = not (args.variant or args.unfused or args.bak_bf16 or args.uncached_worker or
+                 args.iid_queues or args.no_events or args.threads or args.items or
+                 args.max_blocks or args.streaming >= 0)
+    if args.legs == "default":
+        legs = ["cfg2nc", "cfg3", "cfg3iid", "cfg4", "fold", "cfg0", "cfg1"] \
+            if plain and wl.name.startswith("cfg2") else []
+    elif args.legs == "none":
+        legs = []
+    else:
+        legs = [x for x in args.legs.split(",") if x]
+
+    def leg_args(**kw):
+        a = argparse.Namespace(**vars(args))
+        a.fused_worker = a.ordered = a.native_loop = False
+        a.graph = 0
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return a
+
+    all_configs = {}
+    for leg in legs:
+        small = leg in ("cfg0", "cfg1")
+        # the launch-bound 1 MB configurations need more arrivals for a stable figure
+        ls, lw = (max(n_steps, 400), max(n_warm, 50)) if small else (min(n_steps, 40), min(n_warm, 5))
+        if leg == "cfg2nc":
+            rep = measure(leg_args(), "cfg2", min(n_steps, 100), min(n_warm, 10),
+                          uncached_worker=True)
+            if "roofline" in out and "roofline" in rep:
+                r, nc = out["roofline"], rep["roofline"]
+                ceiling = read_probe("practical_ceiling_4r3w_GBs", "25m")
+                r["achieved_nothing_cached"] = nc["achieved"]
+                r["frac_nothing_cached"] = nc["frac"]
+                r["avg_launch_ms_nothing_cached"] = nc["avg_launch_ms"]
+                r["practical_ceiling_GBs"] = ceiling
+                r["practical_ceiling_source"] = ("profiles/membw_probe_mi355x.txt: a plain 4-read/"
+                                                 "3-write streaming kernel with nothing cacheable, "
+                                                 "same vector length (committed; not measured in "
+                                                 "this run)")
+                if ceiling:
+                    r["frac_of_practical"] = nc["achieved"] / ceiling
+                r["which_is_hbm_only"] = (
+                    "frac counts algorithmic bytes against the HBM peak in the workload as it runs: "
+                    "the worker kernel has just read the snapshot and written the gradient, both "
+                    "fit the 256 MB last-level cache, and the push finds them there - that figure "
+                    "is HBM plus last-level cache. frac_nothing_cached is the same kernel with the "
+                    "worker's accesses non-temporal: every byte comes from and goes to HBM; it is "
+                    "the figure to hold against an HBM-bandwidth target.")
+            rep.pop("_wl", None)
+            continue
+        name = {"cfg3iid": "cfg3"}.get(leg, leg)
+        rep = measure(leg_args(native_loop=small), name, ls, lw, arrivals_iid=(leg == "cfg3iid"),
+                      extras=small)
+        rep.pop("_wl", None)
+        all_configs[leg] = leg_summary(rep)
+    if all_configs:
+        all_configs["cfg2"] = leg_summary(out)
+        out["all_configs"] = dict(sorted(all_configs.items()))
+
+    if args.cpu_seconds > 0 and wl.order != "sync":
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds, args.bak_bf16)
     print(json.dumps(out), flush=True)
     return 0

@@ -110,7 +110,14 @@ int dcasgd_push(dcasgd_t h, int worker, const void* grad, void* stream);
  * workers and grads are host arrays of K entries (grads[k]: device pointer
  * as for dcasgd_push).  A queue that repeats a worker is legal: it is split
  * into consecutive launches at each repeat so that the later push sees the
- * refreshed backup.
+ * refreshed backup.  Mind what that means for the caller: Eq. 4.1 compensates
+ * for w - w_bak(m), the distance from the point the gradient was taken at, so
+ * the second gradient of a repeated worker has to have been formed from the
+ * snapshot its first entry's pull left - which does not exist yet when one
+ * call delivers both.  With one gradient in flight per worker (Algorithm 1)
+ * such a queue cannot arise; a caller who does have one delivers it as two
+ * calls, forming the later gradient in between.  Handing over a gradient
+ * taken at the old snapshot is not detected and is compensated too little.
  */
 int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads,
                       int K, void* stream);
@@ -171,12 +178,20 @@ int dcasgd_sync_fold_part(dcasgd_t h, const void* const* grads, int J, int J_tot
                           float eta_hat, const float* kept_w, void* stream);
 
 /*
- * Algorithm 2, "pull request": w_bak(worker) <- w, enqueued on the stream of
- * the most recent init/push on this handle, and returns the device pointer of
- * that backup row, which is what "send w_t back to worker m" hands over.  If
- * the row already equals w (nothing was pushed since it was last refreshed)
- * nothing is launched.  NULL on error.  With DCASGD_BAK_BF16 the row holds
- * bfloat16 values and the pointer is to be cast accordingly.
+ * Algorithm 2, "pull request": w_bak(worker) <- w, and returns the device
+ * pointer of that backup row, which is what "send w_t back to worker m" hands
+ * over.  The call has no stream argument: the copy is enqueued on the stream
+ * of the most recent call on this handle that changed w - dcasgd_init,
+ * dcasgd_push, dcasgd_push_batch, dcasgd_push_synth, dcasgd_run_synth or one
+ * of the dcasgd_sync_fold* calls - and on no other (dcasgd_worker_grad,
+ * dcasgd_grad_sqnorms, dcasgd_set_momentum and dcasgd_bind_counter leave it
+ * alone), so the snapshot is ordered after that update.  A reader of the row
+ * on another stream (a worker kernel, say) has to order itself against that
+ * stream.  If the row already equals w by the host's bookkeeping (nothing was
+ * pushed since it was last refreshed) nothing is launched; after launches the
+ * host did not see (graph replays) dcasgd_set_step resets that bookkeeping.
+ * NULL on error.  With DCASGD_BAK_BF16 the row holds bfloat16 values and the
+ * pointer is to be cast accordingly.
  */
 const float* dcasgd_pull(dcasgd_t h, int worker);
 
@@ -236,11 +251,13 @@ int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* 
  * is the kernel's execution time with no dispatch gap in it.  Events are host
  * objects created on demand and reused.  Do not enable it around launches
  * that are being captured into a HIP graph.
- * dcasgd_timing(h, enable) switches it and forgets unread launches;
+ * dcasgd_timing(h, enable) waits for the timed launches still in flight,
+ * then switches it and forgets unread launches;
  * dcasgd_timing_read waits for the last timed launch, returns the summed
  * kernel time in milliseconds and the number of launches since the last read
  * (host pointers), and starts a new interval.  At most 65536 launches are
- * timed between two reads; later ones run untimed.
+ * timed between two reads; later ones run untimed and are not counted in
+ * *launches, so a reader who knows how many launches it issued can tell.
  */
 int dcasgd_timing(dcasgd_t h, int enable);
 int dcasgd_timing_read(dcasgd_t h, double* total_ms, uint64_t* launches);
@@ -267,7 +284,11 @@ int dcasgd_set_lambda(dcasgd_t h, float lambda0);
  * of 64; items: float4 groups per thread, one of 1, 2, 4; max_blocks: 0 = one
  * block per tile, otherwise blocks loop over tiles; streaming: 0 = plain
  * accesses, 1 = gradient reads and backup reads/writes non-temporal, 2 = w
- * and MeanSquare accesses non-temporal as well.  A zero/negative threads or
+ * and MeanSquare accesses non-temporal as well, 3 = level 2 and in addition
+ * dcasgd_worker_grad reads its snapshot and writes its gradient non-temporally
+ * (at levels 0-2 it leaves both cacheable, so that a push that follows soon
+ * finds them in the last-level cache when they fit; level 3 is the setting
+ * that measures the update against HBM alone).  A zero/negative threads or
  * items keeps the current value.  Defaults: 256 threads (64 for the queue
  * kernel), 2 items, one block per tile, streaming 2.
  */
@@ -281,7 +302,9 @@ int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int st
  * counter = (i/4, push_idx, 0, 0), four normals per counter by Box-Muller in
  * +,-,*,/,sqrt only).  formats: bit 0 set = grad_out is bfloat16[d] (round to
  * nearest even), else float32[d]; bit 1 set = snap is bfloat16[d] (a backup
- * row of a DCASGD_BAK_BF16 server), else float32[d].  All pointers are device
+ * row of a DCASGD_BAK_BF16 server), else float32[d]; bit 2 set = the snapshot
+ * read and the gradient write are non-temporal (nothing of this launch is
+ * meant to stay in the last-level cache), else cacheable.  All pointers are device
  * pointers, 16-byte aligned (8-byte for a bfloat16 vector).  threads/items as
  * in dcasgd_set_launch (0 = defaults).
  */

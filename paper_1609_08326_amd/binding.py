@@ -109,16 +109,19 @@ def _stream_ptr(stream=None) -> int:
 
 
 def synth_grad(snap, hdiag, wstar, sigma: float, seed: int, push_idx: int, out, stream=None,
-               threads: int = 0, items: int = 0) -> None:
+               threads: int = 0, items: int = 0, uncached: bool = False) -> None:
     """Launch the synthetic worker kernel: out <- h*(snap-wstar) + sigma*z(seed, push_idx, i).
-    ``out`` and ``snap`` are float32 or bfloat16 CUDA tensors of the same length."""
+    ``out`` and ``snap`` are float32 or bfloat16 CUDA tensors of the same length.
+    ``uncached``: snapshot read and gradient write non-temporal (nothing is left in the
+    last-level cache for the push that follows)."""
     import torch
     d = snap.numel()
     assert hdiag.numel() == d and wstar.numel() == d and out.numel() == d
     assert hdiag.dtype == wstar.dtype == torch.float32
     assert snap.dtype in (torch.float32, torch.bfloat16)
     assert out.dtype in (torch.float32, torch.bfloat16)
-    formats = int(out.dtype == torch.bfloat16) | (int(snap.dtype == torch.bfloat16) << 1)
+    formats = int(out.dtype == torch.bfloat16) | (int(snap.dtype == torch.bfloat16) << 1) \
+        | (int(bool(uncached)) << 2)
     rc = load().dcasgd_synth_grad(snap.data_ptr(), hdiag.data_ptr(), wstar.data_ptr(),
                                   float(sigma), int(seed), int(push_idx), out.data_ptr(),
                                   formats, d, _stream_ptr(stream),
@@ -162,7 +165,8 @@ class Server:
         _check(lib.dcasgd_bind(self._h, self.w.data_ptr(), self.bak.data_ptr(), self.stride,
                                self.ms.data_ptr() if self.ms is not None else None),
                "dcasgd_bind")
-        _check(lib.dcasgd_init(self._h, _stream_ptr(stream)), "dcasgd_init")
+        self._update_stream = _stream_ptr(stream)       # where dcasgd_pull will enqueue its copy
+        _check(lib.dcasgd_init(self._h, self._update_stream), "dcasgd_init")
 
     def close(self) -> None:
         if getattr(self, "_h", None):
@@ -247,7 +251,8 @@ class Server:
 
     def push(self, worker: int, grad, stream=None) -> None:
         assert grad.is_cuda and grad.dtype == self.grad_dtype and grad.numel() == self.d
-        _check(load().dcasgd_push(self._h, int(worker), grad.data_ptr(), _stream_ptr(stream)),
+        self._update_stream = _stream_ptr(stream)
+        _check(load().dcasgd_push(self._h, int(worker), grad.data_ptr(), self._update_stream),
                "dcasgd_push")
 
     def push_batch(self, workers: Sequence[int], grads: Sequence, stream=None) -> None:
@@ -257,15 +262,17 @@ class Server:
             assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
         wa = (C.c_int * K)(*[int(m) for m in workers])
         ga = (C.c_void_p * K)(*[g.data_ptr() for g in grads])
-        _check(load().dcasgd_push_batch(self._h, wa, ga, K, _stream_ptr(stream)),
+        self._update_stream = _stream_ptr(stream)
+        _check(load().dcasgd_push_batch(self._h, wa, ga, K, self._update_stream),
                "dcasgd_push_batch")
 
     def push_synth(self, worker: int, hdiag, wstar, sigma: float, seed: int, stream=None) -> None:
         """Synthetic worker fused into the push: the gradient of worker's snapshot is
         formed in registers (noise keyed by the server's push counter) and applied."""
         assert hdiag.is_cuda and wstar.is_cuda and hdiag.numel() == wstar.numel() == self.d
+        self._update_stream = _stream_ptr(stream)
         _check(load().dcasgd_push_synth(self._h, int(worker), hdiag.data_ptr(), wstar.data_ptr(),
-                                        float(sigma), int(seed), _stream_ptr(stream)),
+                                        float(sigma), int(seed), self._update_stream),
                "dcasgd_push_synth")
 
     def run_synth(self, workers, hdiag, wstar, sigma: float, seed: int, stream=None) -> None:
@@ -273,8 +280,9 @@ class Server:
         assert hdiag.is_cuda and wstar.is_cuda and hdiag.numel() == wstar.numel() == self.d
         ws = [int(m) for m in workers]
         arr = (C.c_int * len(ws))(*ws)
+        self._update_stream = _stream_ptr(stream)
         _check(load().dcasgd_run_synth(self._h, arr, len(ws), hdiag.data_ptr(), wstar.data_ptr(),
-                                       float(sigma), int(seed), _stream_ptr(stream)),
+                                       float(sigma), int(seed), self._update_stream),
                "dcasgd_run_synth")
 
     def sync_fold(self, grads: Sequence, eta_hat: float, stream=None, workspace=None) -> None:
@@ -285,14 +293,15 @@ class Server:
         for g in grads:
             assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
         ga = (C.c_void_p * J)(*[g.data_ptr() for g in grads])
+        self._update_stream = _stream_ptr(stream)
         if workspace is None:
-            _check(load().dcasgd_sync_fold(self._h, ga, J, float(eta_hat), _stream_ptr(stream)),
+            _check(load().dcasgd_sync_fold(self._h, ga, J, float(eta_hat), self._update_stream),
                    "dcasgd_sync_fold")
             return
         assert workspace.is_cuda and workspace.is_contiguous()
         assert workspace.numel() * workspace.element_size() >= FOLD_WS_BYTES
         _check(load().dcasgd_sync_fold_ordered(self._h, ga, J, float(eta_hat),
-                                               workspace.data_ptr(), _stream_ptr(stream)),
+                                               workspace.data_ptr(), self._update_stream),
                "dcasgd_sync_fold_ordered")
 
     def grad_sqnorms(self, grads: Sequence, workspace, stream=None) -> None:
@@ -316,8 +325,9 @@ class Server:
         import torch
         assert kept_w.is_cuda and kept_w.dtype == torch.float32 and kept_w.numel() == self.d
         ga = (C.c_void_p * J)(*[g.data_ptr() for g in grads])
+        self._update_stream = _stream_ptr(stream)
         _check(load().dcasgd_sync_fold_part(self._h, ga, J, int(J_total), float(eta_hat),
-                                            kept_w.data_ptr(), _stream_ptr(stream)),
+                                            kept_w.data_ptr(), self._update_stream),
                "dcasgd_sync_fold_part")
 
     @staticmethod
@@ -335,8 +345,15 @@ class Server:
         perm = workspace.view(torch.int32)[32:32 + J].cpu().numpy().copy()
         return sq, perm
 
-    def pull(self, worker: int):
-        """Refresh worker's backup from w and return it (a view of row `worker`)."""
+    def pull(self, worker: int, stream=None):
+        """Refresh worker's backup from w and return it (a view of row `worker`).
+        dcasgd_pull takes no stream: the library enqueues the copy on the stream of the
+        last call that changed w.  ``stream`` (default: torch's current stream) states
+        where the caller expects it; if that is another stream the copy would not be
+        ordered with the caller's work, and this raises instead of racing."""
+        if _stream_ptr(stream) != self._update_stream:
+            raise ValueError("pull: the library refreshes the backup on the stream of the last "
+                             "update (init/push/fold); pass that stream, or make it current")
         ptr = load().dcasgd_pull(self._h, int(worker))
         if not ptr:
             raise DcasgdError(load().dcasgd_last_error(self._h), "dcasgd_pull")

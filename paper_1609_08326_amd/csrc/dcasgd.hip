@@ -43,12 +43,12 @@ struct dcasgd_server {
     size_t bak_stride = 0;            // in elements of the backup format
     float* ms = nullptr;
     bool bound = false, ready = false;
-    hipStream_t stream = nullptr;     // stream of the most recent init/push
+    hipStream_t stream = nullptr;     // stream of the most recent call that changed w (init, push*, fold*)
     uint64_t t = 0;                   // pushes applied (Algorithm 2's t)
     std::vector<uint64_t> fresh_at;   // t at which w_bak(m) was last set to w
     int threads = 256, items = 2, max_blocks = 0;
     int batch_threads = 64;           // the queue kernel does 16x the work per lane: one wave per block
-    int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything
+    int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything, 3 worker too
     int norm_blocks = 0;              // grid of the norm kernel, set on first use
     int last_error = DCASGD_OK;
     uint32_t* ctr = nullptr;          // optional device-resident copy of t (low 32 bits)
@@ -491,10 +491,8 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, int J_total, f
           });
         });
         DCASGD_LAUNCH(h, fold_order_kernel, 1, 1024, s, a, ws, (int)nblocks);
-        if (!apply) {                      // norms and ranking only: the model is not touched
-            h->stream = s;
-            return launched(h);
-        }
+        if (!apply)                        // norms and ranking only: the model is not touched,
+            return launched(h);            // and the stream a later pull uses stays what it was
     }
     with_bool(h->adaptive, [&](auto AD) {
      with_bool(h->hp.vel != nullptr, [&](auto MO) {
@@ -597,7 +595,6 @@ int dcasgd_set_momentum(dcasgd_t h, float mu, float* vel, void* stream) {
                        h->d);
     h->hp.mu = mu;
     h->hp.vel = vel;
-    h->stream = s;
     return launched(h);
 }
 
@@ -618,7 +615,6 @@ int dcasgd_bind_counter(dcasgd_t h, uint32_t* counter, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(counter_set_kernel, dim3(1), dim3(64), 0, s, counter, (uint32_t)h->t);
     h->ctr = counter;
-    h->stream = s;
     return launched(h);
 }
 
@@ -651,17 +647,25 @@ int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* 
     hipStream_t s = static_cast<hipStream_t>(stream);
     with_bool(h->grad_bf16, [&](auto BF) {
       with_bool(h->bak_bf16, [&](auto BB) {
-        hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, 1, decltype(BB)::value>),
-                           dim3(grid), dim3(256), 0, s, snap, hdiag, wstar, sigma, k0, k1, t_arg,
-                           static_cast<const uint32_t*>(h->ctr), grad_out, n4, h->d);
+        with_bool(h->streaming >= 3, [&](auto SN) {
+          hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, 1, decltype(BB)::value,
+                                                decltype(SN)::value>),
+                             dim3(grid), dim3(256), 0, s, snap, hdiag, wstar, sigma, k0, k1, t_arg,
+                             static_cast<const uint32_t*>(h->ctr), grad_out, n4, h->d);
+        });
       });
     });
-    h->stream = s;
     return launched(h);
 }
 
 int dcasgd_timing(dcasgd_t h, int enable) {
     if (!h) return DCASGD_EINVAL;
+    // Unread pairs may still belong to launches in flight: wait for the last
+    // one before its events are handed out again (launches on one handle are
+    // issued in order, so the last stop event is the last to complete).
+    if (h->timing_used >= 2 &&
+        hipEventSynchronize(h->timing_events[h->timing_used - 1]) != hipSuccess)
+        return fail(h, DCASGD_EHIP);
     h->timing = enable != 0;
     h->timing_used = 0;
     return DCASGD_OK;
@@ -724,7 +728,7 @@ int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int st
     if (!h) return DCASGD_EINVAL;
     if (threads > 0 && !valid_threads(threads)) return fail(h, DCASGD_EINVAL);
     if (items > 0 && !valid_items(items)) return fail(h, DCASGD_EINVAL);
-    if (max_blocks < 0 || streaming < 0 || streaming > 2) return fail(h, DCASGD_EINVAL);
+    if (max_blocks < 0 || streaming < 0 || streaming > 3) return fail(h, DCASGD_EINVAL);
     if (threads > 0) {
         h->threads = threads;
         h->batch_threads = threads > 256 ? 256 : threads;
@@ -738,8 +742,9 @@ int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int st
 int dcasgd_synth_grad(const void* snap, const float* hdiag, const float* wstar, float sigma,
                       uint64_t seed, uint32_t push_idx, void* grad_out, int formats, size_t d,
                       void* stream, int threads, int items) {
-    if (formats & ~3) return DCASGD_EINVAL;
+    if (formats & ~7) return DCASGD_EINVAL;
     const bool as_bf16 = (formats & 1) != 0, snap_bf16 = (formats & 2) != 0;
+    const bool uncached = (formats & 4) != 0;
     if (!snap || !hdiag || !wstar || !grad_out || d == 0) return DCASGD_EINVAL;
     if (d > ((size_t)1 << 34)) return DCASGD_EINVAL;    // the counter holds i/4 in 32 bits
     if (!std::isfinite(sigma)) return DCASGD_EINVAL;
@@ -760,10 +765,12 @@ int dcasgd_synth_grad(const void* snap, const float* hdiag, const float* wstar, 
     with_bool(as_bf16, [&](auto BF) {
         with_items(items, [&](auto IT) {
           with_bool(snap_bf16, [&](auto BB) {
-            hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, decltype(IT)::value,
-                                                  decltype(BB)::value>),
-                               dim3(grid), dim3(threads), 0, s, snap, hdiag, wstar, sigma, k0, k1,
-                               push_idx, static_cast<const uint32_t*>(nullptr), grad_out, n4, d);
+            with_bool(uncached, [&](auto SN) {
+              hipLaunchKernelGGL((synth_grad_kernel<decltype(BF)::value, decltype(IT)::value,
+                                                    decltype(BB)::value, decltype(SN)::value>),
+                                 dim3(grid), dim3(threads), 0, s, snap, hdiag, wstar, sigma, k0, k1,
+                                 push_idx, static_cast<const uint32_t*>(nullptr), grad_out, n4, d);
+            });
           });
         });
     });

@@ -211,20 +211,44 @@ __device__ __forceinline__ bool in_midrange(float x) {
 }
 
 // in_midrange for four radicands at once, with the four answers folded by
-// integer max/min instead of four compares each: all ranges hold iff the
-// largest offset is below the span, and a significand pattern is hit iff the
-// smallest difference from it is zero.
+// integer max/min instead of four compares each.  The range test needs no
+// subtraction: as unsigned words, every admitted radicand lies in
+// [0x1F800000, 0x5F800000) and every other one (zero, denormal, negative, inf,
+// NaN) outside, so the smallest and the largest word decide.  The significand
+// pattern is hit iff (word + 0x00800001) << 8 is zero (the low 24 bits wrap to
+// zero exactly for 0x7FFFFF; one add-shift instruction), so the smallest of
+// those four decides.
 __device__ __forceinline__ bool quad_in_midrange(const float (&x)[4]) {
-    uint32_t off[4], dif[4];
+    uint32_t u[4], pat[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        const uint32_t u = __float_as_uint(x[c]);
-        off[c] = u - 0x1F800000u;
-        dif[c] = (u & 0x00FFFFFFu) ^ 0x007FFFFFu;
+        u[c] = __float_as_uint(x[c]);
+        pat[c] = (u[c] + 0x00800001u) << 8;
     }
-    const uint32_t far = max(max(off[0], off[1]), max(off[2], off[3]));
-    const uint32_t near = min(min(dif[0], dif[1]), min(dif[2], dif[3]));
-    return far < 0x40000000u && near != 0u;
+    const uint32_t top = max(max(u[0], u[1]), max(u[2], u[3]));
+    const uint32_t bottom = min(min(u[0], u[1]), min(u[2], u[3]));
+    const uint32_t near = min(min(pat[0], pat[1]), min(pat[2], pat[3]));
+    return bottom >= 0x1F800000u && top < 0x5F800000u && near != 0u;
+}
+
+// The wave-wide vote the kernels take: true iff every active lane's four
+// radicands are admitted.  Same three tests as quad_in_midrange, each voted on
+// its own so that the compare results are joined as wave masks on the scalar
+// side and no per-lane boolean has to be materialised.
+__device__ __forceinline__ bool wave_all_in_midrange(const float (&x)[4]) {
+    uint32_t u[4], pat[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        u[c] = __float_as_uint(x[c]);
+        pat[c] = (u[c] + 0x00800001u) << 8;
+    }
+    const uint32_t top = max(max(u[0], u[1]), max(u[2], u[3]));
+    const uint32_t bottom = min(min(u[0], u[1]), min(u[2], u[3]));
+    const uint32_t near = min(min(pat[0], pat[1]), min(pat[2], pat[3]));
+    const uint64_t low = __builtin_amdgcn_ballot_w64(bottom < 0x1F800000u);
+    const uint64_t high = __builtin_amdgcn_ballot_w64(top >= 0x5F800000u);
+    const uint64_t hit = __builtin_amdgcn_ballot_w64(near == 0u);
+    return (low | high | hit) == 0;
 }
 
 // Four parameters at once.  The adaptive lambda needs sqrt and a divide per
@@ -252,8 +276,7 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
             ms[c] = keep + add;
             under[c] = ms[c] + hp.eps;
         }
-        const bool mid = hp.lambda_midrange != 0 && quad_in_midrange(under);
-        if (__builtin_amdgcn_ballot_w64(!mid) == 0) {
+        if (wave_all_in_midrange(under) && hp.lambda_midrange != 0) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 float y;
@@ -284,7 +307,8 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
 // contiguous 1 KiB run.  Blocks walk tiles with stride gridDim.x.
 // NT: 0 = plain accesses, 1 = gradient and backup traffic non-temporal,
 // 2 = w and MeanSquare non-temporal as well (state too large to be re-read
-// from any cache before the next push).
+// from any cache before the next push).  (Level 3 of the launch settings is
+// level 2 here plus a worker kernel that leaves nothing cached either.)
 template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, int ITEMS, int NT, bool BB, bool CHECKED>
 __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w,
                                           float* __restrict__ ms, void* __restrict__ bak,
@@ -802,7 +826,10 @@ __global__ void counter_add_kernel(uint32_t* ctr, uint32_t n) {
 }
 
 // g = h * (snap - wstar) + sigma * z, four parameters per Philox counter.
-template <bool BF16, int ITEMS, bool BB>
+// SNT: snapshot read and gradient write non-temporal as well, so that the
+// launch leaves nothing behind in the last-level cache for the push that
+// follows (the default keeps both cacheable on purpose, see below).
+template <bool BF16, int ITEMS, bool BB, bool SNT>
 __global__ void __launch_bounds__(512)
 synth_grad_kernel(const void* __restrict__ snap, const float* __restrict__ hdiag,
                   const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
@@ -820,7 +847,7 @@ synth_grad_kernel(const void* __restrict__ snap, const float* __restrict__ hdiag
             if (q < n4) {
                 // the snapshot is read again by the push that follows: leave it
                 // cacheable; the loss vectors stream through once per arrival
-                A[j] = load_bak4<BB, false>(snap, q);
+                A[j] = load_bak4<BB, SNT>(snap, q);
                 H[j] = load4<true>(hdiag, q);
                 O[j] = load4<true>(wstar, q);
             } else {
@@ -841,9 +868,10 @@ synth_grad_kernel(const void* __restrict__ snap, const float* __restrict__ hdiag
                     u16x4 pk;
                     pk.x = narrow_bf16(g.x); pk.y = narrow_bf16(g.y);
                     pk.z = narrow_bf16(g.z); pk.w = narrow_bf16(g.w);
-                    reinterpret_cast<u16x4*>(out)[q] = pk;
+                    if constexpr (SNT) __builtin_nontemporal_store(pk, reinterpret_cast<u16x4*>(out) + q);
+                    else reinterpret_cast<u16x4*>(out)[q] = pk;
                 } else {
-                    store4<false>(reinterpret_cast<float*>(out), q, g);
+                    store4<SNT>(reinterpret_cast<float*>(out), q, g);
                 }
             }
         }

@@ -13,7 +13,17 @@
 //   lambda_check predicate N SEED      N random groups of four radicands (edges of
 //                                      the window and the excluded pattern included):
 //                                      the four-at-once admission test against
-//                                      four single ones
+//                                      four single ones, and the wave-wide vote
+//                                      against a vote over the single tests
+//   lambda_check table N SEED FILE     N random (radicand, numerator) pairs over the
+//                                      whole positive finite range (denormals included):
+//                                      writes N records of six 32-bit words to FILE -
+//                                      radicand, numerator, the device's IEEE sqrt and
+//                                      quotient numerator/sqrt, and the short forms'
+//                                      root and quotient (the IEEE values again where
+//                                      the pair is not admitted) - so that a host
+//                                      program can compare all four with its own CPU's
+//                                      IEEE operations
 // Prints the number of cases and of mismatches, the first few mismatches, and
 // exits non-zero if there is any.
 #include <hip/hip_runtime.h>
@@ -21,6 +31,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "dcasgd_kernels.hip.h"
 
@@ -32,6 +43,7 @@ using namespace dcasgd;
 struct Report {
     unsigned long long mismatches;
     unsigned long long skipped;   // radicands the kernels do not take the short path for
+    unsigned long long admitted_waves;   // predicate mode: waves whose vote was "all admitted"
     uint32_t first[8][4];   // radicand bits, numerator bits, got, expected
 };
 
@@ -104,17 +116,55 @@ __global__ void check_predicate(unsigned long long n, uint32_t seed, Report* rep
         float x[4];
         bool each = true;
         uint32_t u = mix((uint32_t)i ^ seed) + (uint32_t)(i >> 32);
+        // Per wave (64 consecutive cases): a third of the waves draw freely, a third
+        // hold admitted radicands only, a third admitted ones except one value of
+        // one lane - so that the wave-wide vote is exercised on both answers.
+        const uint32_t wave_draw = mix((uint32_t)(i >> 6) * 0x9E3779B9u + seed);
+        const uint32_t kind = wave_draw % 3u;
+        const bool odd_one = kind == 2u && (uint32_t)(i & 63u) == ((wave_draw >> 8) & 63u);
         for (int c = 0; c < 4; ++c) {
             u = mix(u + 0x9E3779B9u);
             uint32_t b = u;
+            if (kind != 0u) b = 0x1F800000u + (u & 0x3FFFFFFFu);                        // inside the window
+            const bool steer = kind == 0u || (odd_one && (uint32_t)c == ((wave_draw >> 16) & 3u));
             // steer a share of the draws onto the interesting values
-            if ((u & 0x300u) == 0x100u) b = (b & 0xFF000000u) | 0x007FFFFFu;           // the pattern
-            if ((u & 0x300u) == 0x200u) b = 0x1F800000u + (b & 3u) - 2u;                // lower edge
-            if ((u & 0x300u) == 0x300u) b = 0x5F800000u + (b & 3u) - 2u;                // upper edge
+            if (steer && (u & 0x300u) == 0x100u) b = (b & 0xFF000000u) | 0x007FFFFFu;  // the pattern
+            if (steer && (u & 0x300u) == 0x200u) b = 0x1F800000u + (b & 3u) - 2u;       // lower edge
+            if (steer && (u & 0x300u) == 0x300u) b = 0x5F800000u + (b & 3u) - 2u;       // upper edge
             x[c] = __uint_as_float(b);
             each = each && in_midrange(x[c]);
         }
         if (quad_in_midrange(x) != each) note(rep, __float_as_uint(x[0]), __float_as_uint(x[1]), 0.f, 0.f);
+        // and the wave-wide vote the kernels take against a vote over the single tests
+        const bool wave_wants = __builtin_amdgcn_ballot_w64(!each) == 0;
+        if (wave_wants && (i & 63u) == 0) atomicAdd(&rep->admitted_waves, 1ull);
+        if (wave_all_in_midrange(x) != wave_wants)
+            note(rep, __float_as_uint(x[2]), __float_as_uint(x[3]), 1.f, wave_wants ? 1.f : 0.f);
+    }
+}
+
+__global__ void fill_table(uint32_t n, uint32_t seed, uint32_t* out) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const uint32_t u = mix(i ^ seed), v = mix(u + 0x9E3779B9u);
+        uint32_t xb = u & 0x7FFFFFFFu;                        // positive
+        if ((xb >> 23) == 0xFFu) xb -= 0x00800000u;           // finite
+        if ((u >> 31) != 0u && (i & 7u) == 0u) xb &= 0x007FFFFFu;   // a share of denormals
+        uint32_t ab = v;
+        if (((ab >> 23) & 0xFFu) == 0xFFu) ab -= 0x00800000u;
+        const float x = __uint_as_float(xb), a = __uint_as_float(ab);
+        const float root = __builtin_sqrtf(x);
+        const float quot = a / root;
+        float sroot = root, squot = quot;
+        const float mag = __builtin_fabsf(a);
+        if (in_midrange(x) && mag >= 0x1p-40f && mag <= 0x1p40f) {
+            float y;
+            sroot = root_rn_midrange(x, y);
+            squot = quotient_rn_midrange(a, sroot, y);
+        }
+        uint32_t* rec = out + 6ull * i;
+        rec[0] = xb; rec[1] = ab;
+        rec[2] = __float_as_uint(root); rec[3] = __float_as_uint(quot);
+        rec[4] = __float_as_uint(sroot); rec[5] = __float_as_uint(squot);
     }
 }
 
@@ -181,7 +231,31 @@ int main(int argc, char** argv) {
         const uint32_t seed = (uint32_t)std::strtoull(argv[3], nullptr, 0);
         hipLaunchKernelGGL(check_predicate, dim3(8192), dim3(256), 0, 0, n, seed, rep);
         CHECK(hipGetLastError());
-        return finish("predicate", n, rep);
+        const int rc = finish("predicate", n, rep);
+        Report host;
+        CHECK(hipMemcpy(&host, rep, sizeof(host), hipMemcpyDeviceToHost));
+        std::printf("predicate: %llu of %llu waves voted that all their radicands are admitted\n",
+                    host.admitted_waves, (n + 63) / 64);
+        return rc;
+    }
+    if (!std::strcmp(argv[1], "table") && argc >= 5) {
+        const unsigned long long n = std::strtoull(argv[2], nullptr, 0);
+        const uint32_t seed = (uint32_t)std::strtoull(argv[3], nullptr, 0);
+        if (n == 0 || n > (1ull << 26)) { std::fprintf(stderr, "N must be in [1, 2^26]\n"); return 2; }
+        uint32_t* dev = nullptr;
+        CHECK(hipMalloc(&dev, n * 24));
+        hipLaunchKernelGGL(fill_table, dim3(4096), dim3(256), 0, 0, (uint32_t)n, seed, dev);
+        CHECK(hipGetLastError());
+        CHECK(hipDeviceSynchronize());
+        std::vector<uint32_t> host(n * 6);
+        CHECK(hipMemcpy(host.data(), dev, n * 24, hipMemcpyDeviceToHost));
+        std::FILE* f = std::fopen(argv[4], "wb");
+        if (!f || std::fwrite(host.data(), 24, n, f) != n || std::fclose(f) != 0) {
+            std::fprintf(stderr, "cannot write %s\n", argv[4]);
+            return 2;
+        }
+        std::printf("table: %llu records written to %s\n", n, argv[4]);
+        return 0;
     }
     std::fprintf(stderr, "usage: see the header of lambda_check.hip\n");
     return 2;

@@ -6,13 +6,22 @@
 // the DC-ASGD push is a 4-read/3-write stream, the pull a copy, the worker
 // kernel 3 reads and 1 write.
 //
-// usage: membw_probe [floats per stream, default 25557032]
+// usage: membw_probe [floats per stream, default 25557032] [shapes]
 // Allocates (4 + 4) buffers of that many floats; prints GB/s per pattern.
+// With "shapes" it prints instead, for the 4-read/3-write pattern with
+// non-temporal accesses, what other ways of laying the same work over waves
+// and time achieve: longer contiguous runs per wave, lanes that own
+// consecutive groups, persistent blocks that have the next tile's loads in
+// flight while the current tile is stored, and launches whose waves issue
+// their loads and their stores in alternating windows of the chip-wide
+// 100 MHz clock (every wait is on that free-running counter, never on another
+// wave, and gives up after a fixed number of polls).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <string>
 #include <vector>
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -112,6 +121,208 @@ template <int R, int W> static void pattern(const char* name, Streams a, size_t 
     std::fflush(stdout);
 }
 
+// ---- other shapes of the 4-read/3-write stream ---------------------------------
+// LAYOUT 0: lane l of a tile touches groups l, l + blockDim, ... (the library's);
+//        1: wave v of the block owns ITEMS consecutive runs of 64 groups (ITEMS KiB
+//           contiguous per wave and stream);
+//        2: lane l owns ITEMS consecutive groups (a wave access strides by ITEMS).
+template <int ITEMS, int LAYOUT>
+__device__ __forceinline__ size_t quad_of(size_t tile, int j) {
+    const size_t base = tile * ((size_t)blockDim.x * ITEMS);
+    if constexpr (LAYOUT == 0) return base + (size_t)j * blockDim.x + threadIdx.x;
+    else if constexpr (LAYOUT == 1)
+        return base + ((size_t)(threadIdx.x >> 6) * ITEMS + j) * 64 + (threadIdx.x & 63);
+    else return base + (size_t)threadIdx.x * ITEMS + j;
+}
+
+template <int ITEMS, int LAYOUT>
+__device__ __forceinline__ void load_tile(const Streams& a, size_t tile, size_t n4, f32x4 (&v)[ITEMS][4]) {
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const size_t q = quad_of<ITEMS, LAYOUT>(tile, j);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) v[j][s] = q < n4 ? ld<true>(a.r[s] + q) : f32x4{0, 0, 0, 0};
+    }
+}
+
+template <int ITEMS, int LAYOUT>
+__device__ __forceinline__ void store_tile(const Streams& a, size_t tile, size_t n4, float k,
+                                           const f32x4 (&v)[ITEMS][4]) {
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const size_t q = quad_of<ITEMS, LAYOUT>(tile, j);
+        f32x4 acc = f32x4{k, k, k, k};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc = acc * k + v[j][s];
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+            if (q < n4) st<true>(a.w[s] + q, acc);
+    }
+}
+
+// one block per tile, or (capped grid) blocks that walk tiles
+template <int ITEMS, int LAYOUT>
+__global__ void __launch_bounds__(512) shape_kernel(Streams a, size_t n4, float k) {
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        f32x4 v[ITEMS][4];
+        load_tile<ITEMS, LAYOUT>(a, t, n4, v);
+        store_tile<ITEMS, LAYOUT>(a, t, n4, k, v);
+    }
+}
+
+// persistent blocks, the loads of the next tile issued before the stores of this one
+template <int ITEMS, int LAYOUT>
+__global__ void __launch_bounds__(512) ahead_kernel(Streams a, size_t n4, float k) {
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    size_t t = blockIdx.x;
+    if (t >= ntiles) return;
+    f32x4 cur[ITEMS][4], nxt[ITEMS][4];
+    load_tile<ITEMS, LAYOUT>(a, t, n4, cur);
+    for (;;) {
+        const size_t tn = t + gridDim.x;
+        const bool more = tn < ntiles;
+        if (more) load_tile<ITEMS, LAYOUT>(a, tn, n4, nxt);
+        store_tile<ITEMS, LAYOUT>(a, t, n4, k, cur);
+        if (!more) break;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) cur[j][s] = nxt[j][s];
+        t = tn;
+    }
+}
+
+// Wait until the chip-wide constant-rate counter (100 MHz) is inside the window
+// [lo, hi) of its period (a power of two, given as a mask), polling at most
+// `polls` times: the counter runs by itself, nothing another wave does is
+// waited for, and the loop ends after `polls` rounds whatever it reads.
+__device__ __forceinline__ void wait_window(uint32_t mask, uint32_t lo, uint32_t hi, int polls) {
+    for (int i = 0; i < polls; ++i) {
+        const uint32_t ph = (uint32_t)__builtin_amdgcn_s_memrealtime() & mask;
+        if (ph >= lo && ph < hi) return;
+        __builtin_amdgcn_s_sleep(4);
+    }
+}
+
+// loads are issued in the first `split` ticks of every period, stores in the rest
+template <int ITEMS>
+__global__ void __launch_bounds__(512) windowed_kernel(Streams a, size_t n4, float k, uint32_t mask,
+                                                       uint32_t split, int polls) {
+    const size_t tile_quads = (size_t)blockDim.x * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        f32x4 v[ITEMS][4];
+        wait_window(mask, 0u, split, polls);
+        load_tile<ITEMS, 0>(a, t, n4, v);
+        // the stores below depend on the loads, so the wave first waits for its data
+        f32x4 keep = v[0][0];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) keep = keep + v[j][s];
+        if (keep.x == 123.456f) k += 1.0f;       // uses every loaded value before the wait
+        wait_window(mask, split, mask + 1u, polls);
+        store_tile<ITEMS, 0>(a, t, n4, k, v);
+    }
+}
+
+template <class Launch> static float median_of(Launch&& launch, int reps) {
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    for (int i = 0; i < 3; ++i) launch();
+    std::vector<float> ts;
+    for (int i = 0; i < reps; ++i) {
+        CHECK(hipEventRecord(e0));
+        launch();
+        CHECK(hipEventRecord(e1));
+        CHECK(hipEventSynchronize(e1));
+        float ms;
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        ts.push_back(ms);
+    }
+    CHECK(hipGetLastError());
+    CHECK(hipEventDestroy(e0));
+    CHECK(hipEventDestroy(e1));
+    std::sort(ts.begin(), ts.end());
+    return ts[ts.size() / 2];
+}
+
+template <int ITEMS, int LAYOUT>
+static void shape_row(const char* name, Streams a, size_t n4, int threads, int cap_per_cu, int cus) {
+    const double bytes = 7.0 * (double)n4 * 16.0;
+    const size_t tile_quads = (size_t)threads * ITEMS;
+    const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
+    unsigned grid = (unsigned)ntiles;
+    if (cap_per_cu > 0 && (size_t)cap_per_cu * cus < ntiles) grid = (unsigned)(cap_per_cu * cus);
+    const float t = median_of([&] {
+        hipLaunchKernelGGL((shape_kernel<ITEMS, LAYOUT>), dim3(grid), dim3(threads), 0, 0, a, n4, 0.5f);
+    }, 11);
+    std::printf("%-44s threads %3d items %d grid %7u  %6.1f us  %5.0f GB/s\n", name, threads, ITEMS, grid,
+                t * 1e3, bytes / t / 1e6);
+    std::fflush(stdout);
+}
+
+template <int ITEMS, int LAYOUT>
+static void ahead_row(const char* name, Streams a, size_t n4, int threads, int per_cu, int cus) {
+    const double bytes = 7.0 * (double)n4 * 16.0;
+    const unsigned grid = (unsigned)(per_cu * cus);
+    const float t = median_of([&] {
+        hipLaunchKernelGGL((ahead_kernel<ITEMS, LAYOUT>), dim3(grid), dim3(threads), 0, 0, a, n4, 0.5f);
+    }, 11);
+    std::printf("%-44s threads %3d items %d grid %7u  %6.1f us  %5.0f GB/s\n", name, threads, ITEMS, grid,
+                t * 1e3, bytes / t / 1e6);
+    std::fflush(stdout);
+}
+
+template <int ITEMS>
+static void windowed_row(Streams a, size_t n4, int threads, uint32_t period, uint32_t split) {
+    const double bytes = 7.0 * (double)n4 * 16.0;
+    const size_t tile_quads = (size_t)threads * ITEMS;
+    const unsigned grid = (unsigned)((n4 + tile_quads - 1) / tile_quads);
+    // 4 x 64 cycles per poll: 2000 polls outlast four of the longest periods used here
+    const float t = median_of([&] {
+        hipLaunchKernelGGL((windowed_kernel<ITEMS>), dim3(grid), dim3(threads), 0, 0, a, n4, 0.5f,
+                           period - 1u, split, 2000);
+    }, 11);
+    std::printf("loads/stores in clock windows: period %5.2f us, loads in the first %5.2f us; threads %3d items %d"
+                "  %6.1f us  %5.0f GB/s\n", period * 0.01, split * 0.01, threads, ITEMS, t * 1e3,
+                bytes / t / 1e6);
+    std::fflush(stdout);
+}
+
+static void shapes(Streams a, size_t n4) {
+    int dev = 0, cus = 0;
+    CHECK(hipGetDevice(&dev));
+    CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    std::printf("4 reads + 3 writes, all non-temporal, %d compute units; median of 11 launches\n", cus);
+    shape_row<2, 0>("library shape (1 KiB per wave access)", a, n4, 256, 0, cus);
+    shape_row<4, 0>("library shape", a, n4, 256, 0, cus);
+    shape_row<2, 1>("wave owns 2 KiB per stream", a, n4, 256, 0, cus);
+    shape_row<4, 1>("wave owns 4 KiB per stream", a, n4, 256, 0, cus);
+    shape_row<8, 1>("wave owns 8 KiB per stream", a, n4, 256, 0, cus);
+    shape_row<4, 1>("wave owns 4 KiB per stream", a, n4, 64, 0, cus);
+    shape_row<8, 1>("wave owns 8 KiB per stream", a, n4, 64, 0, cus);
+    shape_row<2, 2>("lane owns 2 consecutive groups", a, n4, 256, 0, cus);
+    shape_row<4, 2>("lane owns 4 consecutive groups", a, n4, 256, 0, cus);
+    shape_row<8, 2>("lane owns 8 consecutive groups", a, n4, 256, 0, cus);
+    shape_row<2, 0>("library shape, blocks walk tiles, 8 per CU", a, n4, 256, 8, cus);
+    shape_row<4, 1>("wave owns 4 KiB, blocks walk tiles, 8 per CU", a, n4, 256, 8, cus);
+    ahead_row<2, 0>("next tile's loads before this tile's stores, 4 per CU", a, n4, 256, 4, cus);
+    ahead_row<2, 0>("next tile's loads before this tile's stores, 8 per CU", a, n4, 256, 8, cus);
+    ahead_row<1, 0>("next tile's loads before this tile's stores, 8 per CU", a, n4, 256, 8, cus);
+    ahead_row<4, 1>("the same, wave owns 4 KiB, 4 per CU", a, n4, 256, 4, cus);
+    ahead_row<2, 0>("next tile's loads before this tile's stores, 16 per CU", a, n4, 128, 16, cus);
+    for (uint32_t period : {256u, 512u, 1024u, 2048u, 4096u})
+        for (uint32_t num : {4u, 5u}) {          // loads get 4/8 or 5/8 of the period
+            windowed_row<2>(a, n4, 256, period, period * num / 8);
+            windowed_row<1>(a, n4, 256, period, period * num / 8);
+        }
+}
+
 int main(int argc, char** argv) {
     const size_t n = argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 25557032ull;
     if (n < 4 || n > (1ull << 32)) {
@@ -130,6 +341,11 @@ int main(int argc, char** argv) {
         a.w[i] = static_cast<f32x4*>(p);
     }
     CHECK(hipDeviceSynchronize());
+    if (argc > 2 && std::string(argv[2]) == "shapes") {
+        std::printf("streams of %zu floats (%.1f MB each)\n", n, n4 * 16 / 1e6);
+        shapes(a, n4);
+        return 0;
+    }
     std::printf("streams of %zu floats (%.1f MB each); median of 15 launches, best of 3 launch shapes\n", n,
                 n4 * 16 / 1e6);
     pattern<1, 0>("1 read", a, n4);

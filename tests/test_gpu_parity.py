@@ -275,6 +275,44 @@ def test_non_default_stream_and_pull_stream_rule():
         assert_same_bits(sv.bak[m, : wl.d].cpu().numpy(), ref.bak(m), "side-stream bak[%d]" % m)
 
 
+def test_pull_follows_the_last_update_not_the_last_call_on_the_handle():
+    """dcasgd_pull enqueues its copy on the stream of the last call that changed w.
+    A worker-gradient launch on another stream in between must not move it there:
+    the copy would then run unordered against pushes still queued on the first
+    stream and hand out a half-updated or stale snapshot."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    wl = small(6_000_011, M=3, T=10)              # pushes long enough to still be queued
+    hd_h, ws_h, order = wl.hdiag(), wl.wstar(), wl.arrivals()
+    a, b = torch.cuda.Stream(), torch.cuda.Stream()
+    hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
+    w = torch.from_numpy(wl.w0()).cuda()
+    g = torch.empty(wl.d, device="cuda")
+    g_other = torch.empty(wl.d, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(a):
+        sv = B.Server(w, wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+        for t, m in enumerate(order):
+            B.synth_grad(sv.snapshot(int(m)), hd, ws, wl.sigma, wl.seed, t, g)
+            sv.push(int(m), g)
+            if t + 1 < len(order):
+                sv.pull(int(m))
+    last = int(order[-1])
+    other = (last + 1) % wl.M
+    with torch.cuda.stream(b):                    # a call on the handle, on another stream
+        sv.worker_grad(other, hd, ws, wl.sigma, wl.seed, g_other)
+        with pytest.raises(ValueError):
+            sv.pull(last)                         # the binding refuses to guess
+    row = sv.pull(last, stream=a)                 # library: still stream a, after the last push
+    a.synchronize()
+    b.synchronize()
+    ref = oracle_run(wl, hd_h, ws_h, order, nthreads=8)
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "w")
+    assert_same_bits(row.cpu().numpy(), ref.w(), "snapshot handed out after the last push")
+    for m in range(wl.M):
+        assert_same_bits(sv.bak[m, : wl.d].cpu().numpy(), ref.bak(m), "bak[%d]" % m)
+
+
 def test_pushes_replay_correctly_from_a_captured_graph():
     """The library's launches can be captured in a HIP graph (no memset nodes, no
     allocation, nothing host-dependent in the kernels).  Replays are checked one
