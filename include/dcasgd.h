@@ -156,6 +156,26 @@ int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float 
                              void* workspace, void* stream);
 
 /*
+ * dcasgd_sync_fold_ordered for callers that cannot allocate device memory and
+ * so have no workspace to hand over: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same three launches, same
+ * result bits; the workspace is a static array inside the library (262656
+ * bytes on every GPU the library runs on, held until the process ends), whose
+ * address is looked up once per GPU in dcasgd_init (or on the first call on a
+ * GPU that saw no dcasgd_init).  The call itself allocates nothing, creates
+ * no events (its launches are not timed even while dcasgd_timing is on) and
+ * records no memset.  Limit: J <= DCASGD_MAX_K gradients, any d; a larger J is
+ * refused with DCASGD_EINVAL, a failed address lookup with DCASGD_EHIP.
+ * Nothing in the array needs clearing between calls (every slot that is read
+ * was written earlier in the same call), but all calls on one GPU - from any
+ * handle or thread - share it: two that overlap in time race, so keep them on
+ * one stream or order them yourself.  The norms and the ranking stay inside
+ * the library; callers who want to read them use dcasgd_sync_fold_ordered.
+ */
+int dcasgd_sync_fold_ordered_static(dcasgd_t h, const void* const* grads, int J, float eta_hat,
+                                    void* stream);
+
+/*
  * Only the first two launches of dcasgd_sync_fold_ordered: the squared norms of
  * J gradients and their ranking are left in the workspace (same layout), the
  * model is not touched and t does not advance.  For callers that rank more

@@ -42,6 +42,8 @@ _PROTOTYPES = {
                                         C.c_float, C.c_void_p, C.c_void_p]),
     "dcasgd_sync_fold_ordered": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_float,
                                            C.c_void_p, C.c_void_p]),
+    "dcasgd_sync_fold_ordered_static": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int,
+                                                  C.c_float, C.c_void_p]),
     "dcasgd_push_synth": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
                                     C.c_uint64, C.c_void_p]),
     "dcasgd_run_synth": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.c_size_t, C.c_void_p,
@@ -303,6 +305,18 @@ class Server:
         _check(load().dcasgd_sync_fold_ordered(self._h, ga, J, float(eta_hat),
                                                workspace.data_ptr(), self._update_stream),
                "dcasgd_sync_fold_ordered")
+
+    def sync_fold_ordered_static(self, grads: Sequence, eta_hat: float, stream=None) -> None:
+        """The ordered fold with the library's own static workspace: nothing is allocated
+        by the call (for callers that cannot allocate); calls on one GPU must not overlap."""
+        J = len(grads)
+        for g in grads:
+            assert g.is_cuda and g.dtype == self.grad_dtype and g.numel() == self.d
+        ga = (C.c_void_p * J)(*[g.data_ptr() for g in grads])
+        self._update_stream = _stream_ptr(stream)
+        _check(load().dcasgd_sync_fold_ordered_static(self._h, ga, J, float(eta_hat),
+                                                      self._update_stream),
+               "dcasgd_sync_fold_ordered_static")
 
     def grad_sqnorms(self, grads: Sequence, workspace, stream=None) -> None:
         """Squared norms and ranking of up to 16 gradients into ``workspace`` (read them

@@ -4,6 +4,7 @@
 #include "../../include/dcasgd.h"
 
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -13,6 +14,35 @@
 #include "dcasgd_kernels.hip.h"
 
 using namespace dcasgd;
+
+// Scratch of dcasgd_sync_fold_ordered_static, the entry point for callers that
+// cannot allocate: one FoldWorkspace (256.5 KB) that every GPU the library
+// runs on holds until the process ends.  In host code the array's name is only
+// a stand-in; the device address is looked up once per GPU (scratch_on_current_
+// device) and that pointer is what kernels receive.
+static __device__ __align__(256) unsigned char scratch[sizeof(FoldWorkspace)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* scratch_address[kMaxDevices] = {};   // device address of `scratch`, per GPU, once known
+std::mutex scratch_lock;
+
+// Address of this GPU's copy of `scratch`; nullptr if the runtime cannot tell.
+void* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> guard(scratch_lock);
+    if (!scratch_address[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        scratch_address[dev] = p;
+    }
+    return scratch_address[dev];
+}
+}  // namespace
 
 // Build-time tuning of the queue kernel: entries per load group, and whether
 // the next group's loads are issued ahead of the current group's arithmetic.
@@ -302,6 +332,9 @@ int dcasgd_init(dcasgd_t h, void* stream) {
     if (!h) return DCASGD_EINVAL;
     if (!h->bound) return fail(h, DCASGD_ESTATE);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // set-up work of dcasgd_sync_fold_ordered_static is done here, so that the
+    // call itself is nothing but launches (a failed lookup is retried there)
+    (void)scratch_on_current_device();
     for (int m = 0; m < h->M; ++m) launch_pull(h, m, s);
     if (h->ms) {
         const size_t n4 = h->d / 4;
@@ -426,9 +459,16 @@ int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdia
 // stands.
 static int fold_impl(dcasgd_t h, const void* const* grads, int J, int J_total, float eta_hat,
                      FoldWorkspace* ws, bool ordered, const float* kept, void* stream,
-                     bool apply = true) {
+                     bool apply = true, bool untimed = false) {
     if (!h) return DCASGD_EINVAL;
     if (!h->ready) return fail(h, DCASGD_ESTATE);
+    // untimed: launches carry no events even while timing is on (events are
+    // created on demand, which is an allocation)
+    struct TimingOff {
+        dcasgd_t h; bool was;
+        TimingOff(dcasgd_t h_, bool off) : h(h_), was(h_->timing) { if (off) h->timing = false; }
+        ~TimingOff() { h->timing = was; }
+    } timing_guard(h, untimed);
     if (!grads || J < 1 || J > DCASGD_MAX_K || J_total < J || !std::isfinite(eta_hat))
         return fail(h, DCASGD_EINVAL);
     if (kept) {
@@ -545,6 +585,18 @@ int dcasgd_sync_fold_ordered(dcasgd_t h, const void* const* grads, int J, float 
     static_assert(sizeof(FoldWorkspace) == DCASGD_FOLD_WS_BYTES, "header and kernels agree");
     return fold_impl(h, grads, J, J, eta_hat, static_cast<FoldWorkspace*>(workspace), true, nullptr,
                      stream);
+}
+
+int dcasgd_sync_fold_ordered_static(dcasgd_t h, const void* const* grads, int J, float eta_hat,
+                                    void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    // the scratch holds one workspace: room for DCASGD_MAX_K gradients, any d
+    if (J > DCASGD_MAX_K) return fail(h, DCASGD_EINVAL);
+    void* ws = scratch_on_current_device();
+    if (!ws) return fail(h, DCASGD_EHIP);
+    return fold_impl(h, grads, J, J, eta_hat, static_cast<FoldWorkspace*>(ws), true, nullptr,
+                     stream, true, true);
 }
 
 const float* dcasgd_pull(dcasgd_t h, int worker) {
