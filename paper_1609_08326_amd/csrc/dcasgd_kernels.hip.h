@@ -173,21 +173,22 @@ __device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
 // rescaling and special-value fix-ups of the general expansions.  While
 // operands and results stay far from both ends of the exponent range the
 // rescaling is the identity, so these give the same bits in ten instructions
-// instead of about thirty.
-// Root: hardware estimate s (within one ulp), its exact residual x - s*s, and
-// one Newton step with h = 1/(2s) taken from the hardware reciprocal of s.
-// Quotient: that same reciprocal y (of s, hence within two ulps of 1/root) is
-// sharpened by one Newton step and seeds a*y; one residual correction follows.
-// (With the unsharpened y and two corrections about two quotients in a
-// billion come out one ulp off.)
+// instead of about thirty, and with ONE transcendental (quarter-rate)
+// instruction: the hardware estimate y of 1/sqrt(x) serves both steps.
+// Root: s = x*y (within a few ulps of sqrt(x)), its exact residual x - s*s,
+// and one Newton step with h = y/2.
+// Quotient: the same y, within two ulps of 1/root, is sharpened by one Newton
+// step and seeds a*y; one residual correction follows.  (With the
+// unsharpened y and two corrections about two quotients in a billion come
+// out one ulp off.)
 // Both are checked against the IEEE operations by the stand-alone checker next
 // to this file: every admitted radicand for the root; every pair of root and
 // numerator significands, 1.4e14 cases, for the quotient; no mismatch.
 __device__ __forceinline__ float root_rn_midrange(float x, float& y) {
-    const float s = __builtin_amdgcn_sqrtf(x);
-    y = __builtin_amdgcn_rcpf(s);
-    const float r = __builtin_fmaf(-s, s, x);
+    y = __builtin_amdgcn_rsqf(x);
+    const float s = x * y;
     const float h = 0.5f * y;
+    const float r = __builtin_fmaf(-s, s, x);
     return __builtin_fmaf(r, h, s);
 }
 
@@ -201,13 +202,16 @@ __device__ __forceinline__ float quotient_rn_midrange(float a, float b, float y)
 }
 
 // Radicands the short forms are used for: 2^-64 <= x < 2^64 (so not zero,
-// denormal, negative, inf or NaN), except an all-ones significand with an even
-// exponent field.  There sqrt(x) lies 2^-50 (relative) below the midpoint of
-// two neighbours and the Newton step lands exactly on it; that one pattern per
-// pair of binades takes the general expansion instead.
+// denormal, negative, inf or NaN), except the two per pair of binades whose
+// root has an all-ones significand (significand 0x7FFFFE or 0x7FFFFF with an
+// even exponent field).  That root is the classical exception of division by
+// iteration: 1/root lies a hair above the midpoint of two neighbours, a
+// reciprocal sharpened by Newton steps still rounds to the lower one, and for
+// a power-of-two numerator the corrected quotient lands exactly on the
+// midpoint.  Those radicands take the general expansion instead.
 __device__ __forceinline__ bool in_midrange(float x) {
     const uint32_t u = __float_as_uint(x);
-    return (u - 0x1F800000u) < 0x40000000u && (u & 0x00FFFFFFu) != 0x007FFFFFu;
+    return (u - 0x1F800000u) < 0x40000000u && (u & 0x00FFFFFEu) != 0x007FFFFEu;
 }
 
 // in_midrange for four radicands at once, with the four answers folded by
@@ -215,20 +219,20 @@ __device__ __forceinline__ bool in_midrange(float x) {
 // subtraction: as unsigned words, every admitted radicand lies in
 // [0x1F800000, 0x5F800000) and every other one (zero, denormal, negative, inf,
 // NaN) outside, so the smallest and the largest word decide.  The significand
-// pattern is hit iff (word + 0x00800001) << 8 is zero (the low 24 bits wrap to
-// zero exactly for 0x7FFFFF; one add-shift instruction), so the smallest of
-// those four decides.
+// patterns are hit iff (word + 0x00800002) << 8 is 0 or 0x100 (the low 24 bits
+// wrap to 0 and 1 exactly for 0x7FFFFE and 0x7FFFFF; one add-shift
+// instruction), so the smallest of those four decides.
 __device__ __forceinline__ bool quad_in_midrange(const float (&x)[4]) {
     uint32_t u[4], pat[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         u[c] = __float_as_uint(x[c]);
-        pat[c] = (u[c] + 0x00800001u) << 8;
+        pat[c] = (u[c] + 0x00800002u) << 8;
     }
     const uint32_t top = max(max(u[0], u[1]), max(u[2], u[3]));
     const uint32_t bottom = min(min(u[0], u[1]), min(u[2], u[3]));
     const uint32_t near = min(min(pat[0], pat[1]), min(pat[2], pat[3]));
-    return bottom >= 0x1F800000u && top < 0x5F800000u && near != 0u;
+    return bottom >= 0x1F800000u && top < 0x5F800000u && near > 0x100u;
 }
 
 // The wave-wide vote the kernels take: true iff every active lane's four
@@ -240,14 +244,14 @@ __device__ __forceinline__ bool wave_all_in_midrange(const float (&x)[4]) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         u[c] = __float_as_uint(x[c]);
-        pat[c] = (u[c] + 0x00800001u) << 8;
+        pat[c] = (u[c] + 0x00800002u) << 8;
     }
     const uint32_t top = max(max(u[0], u[1]), max(u[2], u[3]));
     const uint32_t bottom = min(min(u[0], u[1]), min(u[2], u[3]));
     const uint32_t near = min(min(pat[0], pat[1]), min(pat[2], pat[3]));
     const uint64_t low = __builtin_amdgcn_ballot_w64(bottom < 0x1F800000u);
     const uint64_t high = __builtin_amdgcn_ballot_w64(top >= 0x5F800000u);
-    const uint64_t hit = __builtin_amdgcn_ballot_w64(near == 0u);
+    const uint64_t hit = __builtin_amdgcn_ballot_w64(near <= 0x100u);
     return (low | high | hit) == 0;
 }
 
@@ -301,10 +305,20 @@ __device__ __forceinline__ void apply_push4(const Hyper& hp, const f32x4& g, con
     }
 }
 
+// Which float4 group of a tile a lane handles in its j-th access: lane l touches
+// groups l, l + blockDim.x, ..., so a wave-wide access is one contiguous 1 KiB
+// run and a block covers a contiguous tile.  (Making the ITEMS runs of a wave
+// adjacent - a wave walking ITEMS KiB of every stream - measured the same at
+// 100 MB vectors and 3 % slower at 550 MB ones.)
+template <int ITEMS>
+__device__ __forceinline__ size_t tile_quad(size_t tile_first, int j) {
+    return tile_first + (size_t)j * blockDim.x + threadIdx.x;
+}
+
 // ---- push (optionally fused with the pusher's pull) ----------------------------
-// Work is cut into tiles of blockDim.x * ITEMS float4 groups; lane l of a tile
-// touches groups l, l + blockDim.x, ... so every wave-wide access is one
-// contiguous 1 KiB run.  Blocks walk tiles with stride gridDim.x.
+// Work is cut into tiles of blockDim.x * ITEMS float4 groups; which groups a
+// lane touches is tile_quad's choice; every wave-wide access is one contiguous
+// 1 KiB run.  Blocks walk tiles with stride gridDim.x.
 // NT: 0 = plain accesses, 1 = gradient and backup traffic non-temporal,
 // 2 = w and MeanSquare non-temporal as well (state too large to be re-read
 // from any cache before the next push).  (Level 3 of the launch settings is
@@ -317,7 +331,7 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
     f32x4 W[ITEMS], B[ITEMS], G[ITEMS], S[ITEMS], V[ITEMS];
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
-        const size_t q = first + (size_t)j * blockDim.x;
+        const size_t q = tile_quad<ITEMS>(first, j);
         if (!CHECKED || q < n4) {
             V[j] = load_vel4<MOM>(hp, q);
             G[j] = load_grad4<BF16, (NT >= 1)>(grad, q);
@@ -331,7 +345,7 @@ __device__ __forceinline__ void push_tile(const Hyper& hp, float* __restrict__ w
     }
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
-        const size_t q = first + (size_t)j * blockDim.x;
+        const size_t q = tile_quad<ITEMS>(first, j);
         apply_push4<ADAPTIVE, MOM>(hp, G[j], B[j], W[j], S[j], V[j]);
         if (!CHECKED || q < n4) {
             store_vel4<MOM>(hp, q, V[j]);
@@ -349,7 +363,7 @@ push_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, void* __res
     const size_t tile_quads = (size_t)blockDim.x * ITEMS;
     const size_t ntiles = (n4 + tile_quads - 1) / tile_quads;
     for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const size_t first = tile * tile_quads + threadIdx.x;
+        const size_t first = tile * tile_quads;            // first group of the tile
         if ((tile + 1) * tile_quads <= n4)
             push_tile<ADAPTIVE, MOM, BF16, PULL, ITEMS, NT, BB, false>(hp, w, ms, bak, grad, first, n4);
         else

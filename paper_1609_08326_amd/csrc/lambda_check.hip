@@ -128,7 +128,8 @@ __global__ void check_predicate(unsigned long long n, uint32_t seed, Report* rep
             if (kind != 0u) b = 0x1F800000u + (u & 0x3FFFFFFFu);                        // inside the window
             const bool steer = kind == 0u || (odd_one && (uint32_t)c == ((wave_draw >> 16) & 3u));
             // steer a share of the draws onto the interesting values
-            if (steer && (u & 0x300u) == 0x100u) b = (b & 0xFF000000u) | 0x007FFFFFu;  // the pattern
+            if (steer && (u & 0x300u) == 0x100u)                                      // the patterns and
+                b = (b & 0xFF000000u) | (0x007FFFFCu + ((u >> 10) & 3u) + ((u >> 12) & 1u));   // their neighbours
             if (steer && (u & 0x300u) == 0x200u) b = 0x1F800000u + (b & 3u) - 2u;       // lower edge
             if (steer && (u & 0x300u) == 0x300u) b = 0x5F800000u + (b & 3u) - 2u;       // upper edge
             x[c] = __uint_as_float(b);

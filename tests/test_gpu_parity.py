@@ -425,19 +425,25 @@ def test_two_servers_on_two_streams_do_not_disturb_each_other():
             assert_same_bits(svs[i].bak[m, : wl.d].cpu().numpy(), ref.bak(m), "server %d bak[%d]" % (i, m))
 
 
-def test_radicand_that_the_short_square_root_must_not_take():
-    """MeanSquare + eps = 1 - 2^-24 (all-ones significand, even exponent field) is the one
-    radicand pattern whose root lies 2^-50 below a rounding midpoint; the kernels send it
-    down the general expansion.  Built here on purpose: m = 0, eps = 1 - 2^-23 and
-    g = +-2^-12 give exactly that radicand; lambda0 = 2^24, eta = 1 and a model of the
-    gradient's own size make the last bit of lambda visible in w: with a root of exactly 1
-    about half of those parameters would come out different (checked below on the host)."""
+@pytest.mark.parametrize("pattern", [0x3F7FFFFF, 0x3F7FFFFE])
+def test_radicands_that_the_short_forms_must_not_take(pattern):
+    """The two radicands per pair of binades whose square root has an all-ones
+    significand: MeanSquare + eps = 1 - 2^-24 (its root lies 2^-50 below a rounding
+    midpoint) and 1 - 2^-23 (root 1 - 2^-24; for a power-of-two lambda0 the quotient
+    lambda0/root lies a hair above a rounding midpoint, the classical hard case of
+    division by iteration).  The kernels send both down the general expansions.  Built
+    here on purpose: m = 0, g = +-2^-12 and eps = 1 - 2^-23, respectively 1 - 3*2^-24,
+    give exactly those radicands; lambda0 = 2^24, eta = 1 and a model of the gradient's
+    own size make the last bit of lambda visible in w: with lambda = lambda0 exactly
+    (what a root of 1, or a quotient rounded down, would give) about half of those
+    parameters would come out different (checked below on the host)."""
     import torch
     from paper_1609_08326_amd import binding as B
     F = np.float32
     rng = np.random.default_rng(41)
     d = 70003
-    eps, lam0, eta = F(1.0) - F(2.0 ** -23), F(2.0 ** 24), F(1.0)
+    eps = F(1.0) - F(2.0 ** -23) if pattern == 0x3F7FFFFF else F(1.0) - F(3 * 2.0 ** -24)
+    lam0, eta = F(2.0 ** 24), F(1.0)
     w0 = (F(2.0 ** -12) * rng.standard_normal(d)).astype(F)
     sv = B.Server(torch.from_numpy(w0).cuda(), 2, float(eta), float(lam0), B.MODE_A, 0.0, float(eps))
     ref = oracle.Server(w0, 2, float(eta), float(lam0), oracle.MODE_A, 0.0, float(eps))
@@ -452,10 +458,11 @@ def test_radicand_that_the_short_square_root_must_not_take():
     ref.push(1, g)
     torch.cuda.synchronize()
     under = (ref.ms() + eps).astype(F)
-    assert np.all(under[hit].view(np.uint32) == 0x3F7FFFFF)       # the pattern was really produced
+    assert np.all(under[hit].view(np.uint32) == pattern)          # the radicand was really produced
     assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "ms")
     assert_same_bits(sv.w.cpu().numpy(), ref.w(), "w with the excluded radicand in every wave")
-    # what a root of exactly 1 for those radicands would have given
+    # what lambda = lambda0 for those radicands would have given
+    assert np.all((lam0 / np.sqrt(under[hit])).astype(F) != lam0)
     lam = np.where(hit, lam0, lam0 / np.sqrt(under)).astype(F)
     g2 = g * g
     c1 = lam * g2
