@@ -503,6 +503,13 @@ def leg_summary(rep: dict) -> dict:
             d.update({"bound": "launch latency", "frac": None, "achieved_GBs": r["achieved"]})
         else:
             d.update({"bound": "hbm", "frac": r["frac"], "achieved_GBs": r["achieved"]})
+            if r["kernel"] == "push_fused" and rep["config"]["variant"] == "DC-ASGD-a":
+                # the probe's figure for the same 4-read/3-write mix at the nearer vector length
+                ceiling = read_probe("practical_ceiling_4r3w_GBs",
+                                     "25m" if rep["config"]["d"] < 60_000_000 else "138m")
+                if ceiling:
+                    d["practical_ceiling_GBs"] = ceiling
+                    d["frac_of_practical"] = r["achieved"] / ceiling
     for k in ("native_loop_path", "fused_worker_path"):
         if k in rep:
             d[k] = {"value": rep[k]["value"], "ms_per_step": rep[k]["ms_per_step"]}
