@@ -80,7 +80,7 @@ struct dcasgd_server {
     int push_items = 2;               // items of the push and pull kernels (size rule in dcasgd_create)
     int batch_threads = 64;           // the queue kernel does 16x the work per lane: one wave per block
     int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything, 3 worker too
-    int norm_blocks = 0;              // grid of the norm kernel, set on first use
+    int norm_blocks = 0;              // grid of the norm kernel, set by dcasgd_init
     int last_error = DCASGD_OK;
     uint32_t* ctr = nullptr;          // optional device-resident copy of t (low 32 bits)
     // optional per-launch timing of the server-update kernels
@@ -235,6 +235,22 @@ void launch_push(dcasgd_t h, int worker, const void* grad, bool fuse_pull, hipSt
     });
 }
 
+// Grid of the norm kernel.  A pure read stream is fastest with few, long-lived
+// blocks: two per compute unit measured best on MI355X (one 102 MB vector in
+// 15 us).  Asked once per handle, in dcasgd_init, so that the fold calls
+// themselves make no device queries.
+bool size_norm_grid(dcasgd_t h) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus < 1) {
+        (void)hipGetLastError();
+        return false;
+    }
+    h->norm_blocks = 2 * cus < FOLD_WS_BLOCKS ? 2 * cus : FOLD_WS_BLOCKS;
+    return true;
+}
+
 // entries [k0, k1) of a queue; their workers are pairwise distinct
 void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int k0, int k1,
                   hipStream_t s) {
@@ -340,6 +356,7 @@ int dcasgd_init(dcasgd_t h, void* stream) {
     // set-up work of dcasgd_sync_fold_ordered_static is done here, so that the
     // call itself is nothing but launches (a failed lookup is retried there)
     (void)scratch_on_current_device();
+    (void)size_norm_grid(h);
     for (int m = 0; m < h->M; ++m) launch_pull(h, m, s);
     if (h->ms) {
         const size_t n4 = h->d / 4;
@@ -515,16 +532,7 @@ static int fold_impl(dcasgd_t h, const void* const* grads, int J, int J_total, f
     const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (ordered) {
-        if (h->norm_blocks == 0) {
-            // A pure read stream is fastest with few, long-lived blocks: two per
-            // compute unit measured best on MI355X (one 102 MB vector in 15 us).
-            int dev = 0, cus = 0;
-            if (hipGetDevice(&dev) != hipSuccess ||
-                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-                cus < 1)
-                return fail(h, DCASGD_EHIP);
-            h->norm_blocks = 2 * cus < FOLD_WS_BLOCKS ? 2 * cus : FOLD_WS_BLOCKS;
-        }
+        if (h->norm_blocks == 0 && !size_norm_grid(h)) return fail(h, DCASGD_EHIP);
         const int cap = (h->max_blocks > 0 && h->max_blocks < h->norm_blocks) ? h->max_blocks
                                                                               : h->norm_blocks;
         const unsigned nblocks = grid_for(n4, 256 * DCASGD_NORM_ITEMS, cap);

@@ -34,7 +34,10 @@ def check(sv, ref, wl, tag):
         assert_same_bits(sv.bak[m, : wl.d].cpu().numpy(), ref.bak(m), tag + " bak[%d]" % m)
 
 
-def test_counter_bound_eager_path_matches_oracle():
+@pytest.mark.parametrize("streaming", [2, 3])
+def test_counter_bound_eager_path_matches_oracle(streaming):
+    """(streaming 3: the worker kernel issued through the handle leaves nothing cached;
+    a cache policy changes no bit.)"""
     import torch
     from paper_1609_08326_amd import binding as B
     wl = workload()
@@ -42,6 +45,7 @@ def test_counter_bound_eager_path_matches_oracle():
     hd, ws = torch.from_numpy(hd_h).cuda(), torch.from_numpy(ws_h).cuda()
     sv = B.Server(torch.from_numpy(wl.w0()).cuda(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m,
                   wl.eps, pull_on_push=True)
+    sv.set_launch(streaming=streaming)
     g = torch.empty(wl.d, device="cuda")
     sv.push_synth(int(order[0]), hd, ws, wl.sigma, wl.seed)       # t = 1 before binding
     sv.bind_counter()

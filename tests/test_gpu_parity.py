@@ -46,6 +46,11 @@ def test_synth_grad_matches_oracle():
                 got = out.float().cpu().numpy()
                 ref = oracle.synth_grad(snap, h, ws, 0.01, 0xDEADBEEF12345, 9, as_bf16=bf16)
                 assert_same_bits(got, ref, "synth_grad d=%d bf16=%s" % (d, bf16))
+                out.zero_()                      # the cache policy of the launch changes no bit
+                B.synth_grad(torch.from_numpy(snap).cuda(), torch.from_numpy(h).cuda(),
+                             torch.from_numpy(ws).cuda(), 0.01, 0xDEADBEEF12345, 9, out,
+                             threads=threads, items=items, uncached=True)
+                assert_same_bits(out.float().cpu().numpy(), ref, "uncached synth_grad d=%d" % d)
 
 
 @pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
@@ -57,7 +62,8 @@ def test_small_sizes_every_tail(mode, bf16, fused):
         for launch in (None, dict(threads=64, items=1), dict(threads=128, items=4),
                        dict(threads=512, items=2, max_blocks=3),
                        dict(threads=256, items=2, streaming=0),
-                       dict(threads=256, items=1, streaming=2)):
+                       dict(threads=256, items=1, streaming=2),
+                       dict(threads=256, items=4, streaming=3)):
             wl = small(d, mode=mode, bf16=bf16)
             say("small d=%d mode=%d bf16=%s fused=%s launch=%s" % (d, mode, bf16, fused, launch))
             run = DeviceRun(wl, fused=fused, launch=launch)

@@ -10,6 +10,8 @@ import sys
 import numpy as np
 import pytest
 
+import oracle
+
 from gpu_harness import assert_same_bits
 
 pytestmark = pytest.mark.gpu
@@ -72,3 +74,41 @@ def test_static_workspace_fold_refuses_a_list_longer_than_its_limit():
     assert torch.equal(sv.w, before), "a refused call launches nothing"
     assert lib.dcasgd_sync_fold_ordered_static(sv._h, ga, 0, 0.1, None) == B.EINVAL
     assert lib.dcasgd_sync_fold_ordered_static(None, ga, 1, 0.1, None) == B.EINVAL
+
+
+def test_static_workspace_fold_replays_from_a_captured_graph():
+    """What the entry point is for: captured into a HIP graph (nothing in the call
+    allocates, queries the device or records a memset) and replayed, with eager work and
+    synchronisation between the replays; every replay is checked against the oracle's
+    fold of the same gradients in ascending-norm order."""
+    import torch
+    from paper_1609_08326_amd import binding as B
+    rng = np.random.default_rng(43)
+    d, J = 300_007, 6
+    w0 = rng.standard_normal(d).astype(np.float32)
+    scale = (rng.permutation(J).astype(np.float32) * 0.02 + 0.01)[:, None]
+    g = (scale * rng.standard_normal((J, d))).astype(np.float32)
+    order = np.argsort(oracle.grad_sqnorms(g), kind="stable")
+    side = torch.cuda.Stream()
+    dev = [torch.from_numpy(x).cuda() for x in g]
+    other = torch.zeros(1 << 20, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        sv = B.Server(torch.from_numpy(w0).cuda(), 1, 0.1, 2.0, B.MODE_A, 0.95, 1e-7)
+        sv.sync_fold_ordered_static(dev, 0.05 * J)          # eager once on the capture stream
+    side.synchronize()
+    ref = oracle.Server(w0, 1, 0.1, 2.0, oracle.MODE_A, 0.95, 1e-7)
+    ref.sync_fold(g[order], 0.05 * J)
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "eager w")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sv.sync_fold_ordered_static(dev, 0.05 * J)
+    for r in range(3):
+        say("static-workspace fold, graph replay %d" % r)
+        graph.replay()
+        torch.cuda.synchronize()
+        ref.sync_fold(g[order], 0.05 * J)
+        assert_same_bits(sv.w.cpu().numpy(), ref.w(), "replay %d w" % r)
+        assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "replay %d ms" % r)
+        other.add_(1.0)                                      # unrelated eager work between replays
+        torch.cuda.synchronize()
