@@ -75,6 +75,23 @@ def read_probe(key: str, size: str):
         return None
 
 
+def device_clock_hz(lib, device_index: int):
+    """Peak engine clock the HIP runtime reports for the device (hipDeviceGetAttribute,
+    hipDeviceAttributeClockRate: the sixth enumerator of the public header, kilohertz),
+    resolved through the already loaded library's dependency on the runtime; None if the
+    runtime does not answer."""
+    import ctypes
+    try:
+        fn = lib.hipDeviceGetAttribute
+    except AttributeError:
+        return None
+    fn.restype, fn.argtypes = ctypes.c_int, [ctypes.POINTER(ctypes.c_int), ctypes.c_int, ctypes.c_int]
+    khz = ctypes.c_int(0)
+    if fn(ctypes.byref(khz), 5, int(device_index)) != 0 or khz.value <= 0:
+        return None
+    return khz.value * 1e3
+
+
 def cpu_baseline(wl, target_s: float, bak_bf16: bool = False):
     """Time the oracle (as it stands) on a bounded sample of the workload:
     a leading slice of the parameter vector, the workload's arrival order
@@ -330,6 +347,10 @@ def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: 
                            "algorithmic_bytes_per_launch": launch_bytes,
                            "bytes_per_element_update": bpu}
         valu = read_profile(pname, "valu_instr_per_launch")
+        # the same vector-issue peak at the engine clock and unit count this device reports
+        props = torch.cuda.get_device_properties(dev)
+        clock_hz = device_clock_hz(B.load(), dev.index or 0)
+        device_peak = props.multi_processor_count * 4 * 16 * clock_hz / 1e12 if clock_hz else None
         if valu:
             # vector issue: measured wavefront VALU instructions per launch x 64 lanes / time
             lane_rate = valu * 64 / (push_ms * 1e-3) / 1e12
@@ -337,6 +358,10 @@ def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: 
             out["roofline"]["alu_peak_Tlane_per_s"] = VALU_PEAK_TLANE
             out["roofline"]["alu_frac"] = lane_rate / VALU_PEAK_TLANE
             out["roofline"]["valu_instr_per_element_update"] = valu * 64 / (wl.d * K)
+            if device_peak:
+                out["roofline"]["alu_peak_at_device_reported_clock"] = {
+                    "compute_units": props.multi_processor_count, "clock_GHz": clock_hz / 1e9,
+                    "peak_Tlane_per_s": device_peak, "frac": lane_rate / device_peak}
         if sync and valu:
             # the fold moves 5 B per update and is bound by vector issue instead
             hbm = out["roofline"]
@@ -347,6 +372,8 @@ def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: 
                                "avg_launch_ms": push_ms,
                                "hbm_achieved_GBs": achieved, "hbm_frac": achieved / HBM_PEAK_GBS,
                                "valu_instr_per_element_update": valu * 64 / (wl.d * K),
+                               "alu_peak_at_device_reported_clock":
+                                   hbm.get("alu_peak_at_device_reported_clock"),
                                "algorithmic_bytes_per_launch": launch_bytes,
                                "bytes_per_element_update": bpu}
         out["server_update_only"] = {"value": wl.d * K / (push_ms * 1e-3),

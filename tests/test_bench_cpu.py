@@ -33,3 +33,11 @@ def test_profile_figures_are_read_from_the_committed_summaries():
     assert bench.read_profile("push_fused_cfg2") > 7.0e8
     assert bench.read_profile("sync_fold_J16_fold", "valu_instr_per_launch") > 1e8
     assert bench.read_profile("no_such_kernel") is None
+
+
+def test_practical_ceilings_are_read_from_the_probe_summary():
+    import bench
+    for size in ("25m", "138m"):
+        v = bench.read_probe("practical_ceiling_4r3w_GBs", size)
+        assert v is not None and 5000.0 < v < 8000.0, (size, v)
+    assert bench.read_probe("no_such_key", "25m") is None

@@ -1,7 +1,9 @@
 """The C ABI used from plain C99, with hipMalloc'ed memory and neither Python
-nor PyTorch in the process: the client next to the library runs three cases
-with closed-form results (ASGD for lambda = 0, pull semantics, one
-delay-compensated update worked by hand) and the error paths."""
+nor PyTorch in the process: the client next to the library runs cases with
+closed-form results (ASGD for lambda = 0, pull semantics, one delay-compensated
+update worked by hand, the synchronous fold in the caller's order and ranked by
+norm with the caller's and with the library's static workspace) and the error
+paths."""
 import os
 import subprocess
 import sys

@@ -394,6 +394,20 @@ def test_per_launch_timing_counts_launches_and_changes_nothing():
     sv2.push(1, g)
     assert sv2.timing_read_each(capacity=1).size == 1     # a short buffer still ends the interval
     assert sv2.timing_read() == (0.0, 0)
+    # switching timing on again while timed launches are still in flight: their events are
+    # handed out again, so the call first waits for them; the next interval is its own
+    big = small(4_000_003, M=2, T=4)
+    sv3 = B.Server(torch.zeros(big.d, device="cuda"), 2, 0.1, 2.0, B.MODE_A, 0.95, 1e-7,
+                   pull_on_push=True)
+    gb = torch.full((big.d,), 1e-3, device="cuda")
+    sv3.timing(True)
+    for _ in range(6):
+        sv3.push(0, gb)
+    sv3.timing(True)                             # unread launches forgotten, none left in flight
+    for _ in range(3):
+        sv3.push(1, gb)
+    each = sv3.timing_read_each()
+    assert each.size == 3 and np.all(each > 0.0) and float(each.max()) < 5.0
 
 
 def test_two_servers_on_two_streams_do_not_disturb_each_other():
