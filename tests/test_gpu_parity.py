@@ -535,6 +535,21 @@ def test_every_bit_of_lambda_reaches_the_model():
     assert int(np.sum(out[0].view(np.uint32) != out[1].view(np.uint32))) > d // 3
 
 
+def test_config3_size_with_independent_arrivals_sampled():
+    """Configuration 3's other reading, which bench.py times as leg `cfg3iid`: queues of 16
+    filled by independent uniform arrivals, so that workers repeat inside a queue and the
+    queue is delivered in pieces of distinct workers (each piece's gradients formed after
+    the previous piece has run).  Full size, 96 arrivals, a seeded sample of elements."""
+    wl = W.CONFIGS[3].replace(name="cfg3_iid", order="iid", T=96)
+    say("full-size sampled %s" % wl.name)
+    run = DeviceRun(wl, batched=True)
+    queues = [run.arrivals[i:i + wl.K] for i in range(0, wl.T, wl.K)]
+    assert all(len(set(q.tolist())) < wl.K for q in queues), "every queue should repeat a worker"
+    idx = wl.sample_indices(150_000, edge=4096)
+    ref = oracle_run(wl, run.hdiag_host, run.wstar_host, run.arrivals, idx=idx, nthreads=16)
+    compare(run, ref, idx=idx, tag=wl.name)
+
+
 def test_config2_every_element_for_a_stretch_of_pushes():
     """Configuration 2 at full size and in bench.py's launch shape, the oracle on ALL
     25.6 M parameters (16 host threads over element chunks) for the first 48 arrivals:
