@@ -1,6 +1,6 @@
 """Differential test of the whole C ABI as a state machine: a seeded random
 sequence of calls (pushes, queues with and without repeated workers, pulls,
-folds in the caller's order and ranked by norm, worker-fused pushes, worker
+folds in the caller's order and ranked by norm (caller's and static workspace), worker-fused pushes, worker
 gradient + push, step-size and momentum changes) is applied to the library and,
 call by call, to the oracle; every vector of the server state must agree bit
 for bit at checkpoints and at the end."""
@@ -76,8 +76,8 @@ def test_random_call_sequence(seed):
         return gt.float().numpy(), [gt[j].contiguous().cuda() for j in range(n)]
 
     ops = ["push", "batch", "batch_repeat", "pull", "fold", "fold_ranked", "push_synth",
-           "worker_then_push", "eta", "momentum", "lambda", "fold_parts"]
-    weights = np.array([4, 2, 1, 2, 1, 1, 2, 1, 1, 1, 1, 1], dtype=float)
+           "worker_then_push", "eta", "momentum", "lambda", "fold_parts", "fold_static"]
+    weights = np.array([4, 2, 1, 2, 1, 1, 2, 1, 1, 1, 1, 1, 1], dtype=float)
     trace = []
     for step in range(90):
         op = str(rng.choice(ops, p=weights / weights.sum()))
@@ -119,6 +119,14 @@ def test_random_call_sequence(seed):
                 want = np.argsort(oracle.grad_sqnorms(g), kind="stable")
                 assert perm.tolist() == want.tolist(), (step, perm, want)
                 ref.sync_fold(g[want], eta_hat)
+        elif op == "fold_static":
+            # the ranked fold with the library's static workspace: the order is not handed
+            # out, it shows in the folded model
+            J = int(rng.integers(1, 17))
+            g, dev = gradients(J)
+            eta_hat = float(np.float32(0.05 * J))
+            sv.sync_fold_ordered_static(dev, eta_hat)
+            ref.sync_fold(g[np.argsort(oracle.grad_sqnorms(g), kind="stable")], eta_hat)
         elif op == "fold_parts":
             J = int(rng.integers(17, 41))
             g, dev = gradients(J)
