@@ -5,7 +5,8 @@
  * Descent with Delay Compensation" (Zheng et al.): Algorithm 2 with the update
  * rule of Eq. 4.1, with a constant lambda (DC-ASGD-c) or the adaptive lambda
  * of Eq. 18 (DC-ASGD-a).  Every step runs in hand-written HIP kernels; the
- * library allocates no device memory and owns nothing but the small handle.
+ * library calls no device allocator and owns nothing but the small handle
+ * and one static 256.5 KB device array (see dcasgd_sync_fold_ordered_static).
  *
  * Conventions
  *   - "device pointer": memory of the GPU that is current when the call is
