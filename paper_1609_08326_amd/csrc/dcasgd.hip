@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/dcasgd.h: argument validation,
 // bookkeeping of Algorithm 2's counter t and of which backups are current,
-// and kernel launches.  No device memory is allocated here.
+// and kernel launches.  No allocator is called here; the one device array the
+// library owns is the static workspace declared below.
 #include "../../include/dcasgd.h"
 
 #include <cmath>
