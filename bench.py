@@ -638,10 +638,13 @@ def main() -> int:
                 r["frac_nothing_cached"] = nc["frac"]
                 r["avg_launch_ms_nothing_cached"] = nc["avg_launch_ms"]
                 r["practical_ceiling_GBs"] = ceiling
-                r["practical_ceiling_source"] = ("profiles/membw_probe_mi355x.txt: a plain 4-read/"
-                                                 "3-write streaming kernel with nothing cacheable, "
-                                                 "same vector length (committed; not measured in "
-                                                 "this run)")
+                r["probe_sustained_GBs"] = read_probe("sustained_4r3w_GBs", "25m")
+                r["practical_ceiling_source"] = ("profiles/membw_probe_mi355x.txt: plain 4-read/"
+                                                 "3-write streaming kernels with nothing cacheable, "
+                                                 "same vector length: the best figure any variant "
+                                                 "reached, and the rate the library's shape sustains "
+                                                 "over two seconds (committed; not measured in this "
+                                                 "run)")
                 if ceiling:
                     r["frac_of_practical"] = nc["achieved"] / ceiling
                 r["which_is_hbm_only"] = (

@@ -6,7 +6,7 @@
 // the DC-ASGD push is a 4-read/3-write stream, the pull a copy, the worker
 // kernel 3 reads and 1 write.
 //
-// usage: membw_probe [floats per stream, default 25557032] [shapes]
+// usage: membw_probe [floats per stream, default 25557032] [shapes | stagger | sustain]
 // Allocates (4 + 4) buffers of that many floats; prints GB/s per pattern.
 // With "shapes" it prints instead, for the 4-read/3-write pattern with
 // non-temporal accesses, what other ways of laying the same work over waves
@@ -16,6 +16,10 @@
 // their loads and their stores in alternating windows of the chip-wide
 // 100 MHz clock (every wait is on that free-running counter, never on another
 // wave, and gives up after a fixed number of polls).
+// With "stagger" it shifts the seven streams of that pattern against each other
+// by multiples of a step, to see whether their relative placement matters;
+// with "sustain" it repeats that launch for about two seconds and prints the rate
+// over time.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -229,6 +233,37 @@ __global__ void __launch_bounds__(512) windowed_kernel(Streams a, size_t n4, flo
     }
 }
 
+// R read streams and 7 - R write streams over eight buffers (reads take the first R,
+// writes the last 7 - R, so no buffer is both): how the rate depends on the share of
+// writes when the number of streams stays the same.
+struct Eight { f32x4* p[8]; };
+
+template <int R>
+__global__ void __launch_bounds__(256) share_kernel(Eight a, size_t n4, float k) {
+    constexpr int W = 7 - R;
+    const size_t q0 = (size_t)blockIdx.x * (blockDim.x * 2) + threadIdx.x;
+    f32x4 v[2][R > 0 ? R : 1];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const size_t q = q0 + (size_t)j * blockDim.x;
+#pragma unroll
+        for (int s = 0; s < R; ++s) v[j][s] = q < n4 ? ld<true>(a.p[s] + q) : f32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const size_t q = q0 + (size_t)j * blockDim.x;
+        f32x4 acc = f32x4{k, k, k, k};
+#pragma unroll
+        for (int s = 0; s < R; ++s) acc = acc * k + v[j][s];
+        if (W == 0) {
+            if (acc.x == 123.456f && q < n4) a.p[7][q] = acc;
+        }
+#pragma unroll
+        for (int s = 0; s < W; ++s)
+            if (q < n4) st<true>(a.p[8 - W + s] + q, acc);
+    }
+}
+
 template <class Launch> static float median_of(Launch&& launch, int reps) {
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0));
@@ -294,6 +329,17 @@ static void windowed_row(Streams a, size_t n4, int threads, uint32_t period, uin
     std::fflush(stdout);
 }
 
+template <int R> static void share_row(Eight e, size_t n4) {
+    const double bytes = 7.0 * (double)n4 * 16.0;
+    const unsigned grid = (unsigned)((n4 + 511) / 512);
+    const float t = median_of([&] {
+        hipLaunchKernelGGL((share_kernel<R>), dim3(grid), dim3(256), 0, 0, e, n4, 0.5f);
+    }, 11);
+    std::printf("%d read + %d write streams (%2.0f %% of the bytes written)   %6.1f us  %5.0f GB/s\n", R, 7 - R,
+                100.0 * (7 - R) / 7.0, t * 1e3, bytes / t / 1e6);
+    std::fflush(stdout);
+}
+
 static void shapes(Streams a, size_t n4) {
     int dev = 0, cus = 0;
     CHECK(hipGetDevice(&dev));
@@ -316,11 +362,76 @@ static void shapes(Streams a, size_t n4) {
     ahead_row<1, 0>("next tile's loads before this tile's stores, 8 per CU", a, n4, 256, 8, cus);
     ahead_row<4, 1>("the same, wave owns 4 KiB, 4 per CU", a, n4, 256, 4, cus);
     ahead_row<2, 0>("next tile's loads before this tile's stores, 16 per CU", a, n4, 128, 16, cus);
+    Eight e;
+    for (int i = 0; i < 4; ++i) { e.p[i] = const_cast<f32x4*>(a.r[i]); e.p[4 + i] = a.w[i]; }
+    std::printf("seven streams, 256 threads x 2 groups, all non-temporal, by share of writes:\n");
+    share_row<7>(e, n4); share_row<6>(e, n4); share_row<5>(e, n4); share_row<4>(e, n4);
+    share_row<3>(e, n4); share_row<2>(e, n4); share_row<1>(e, n4); share_row<0>(e, n4);
     for (uint32_t period : {256u, 512u, 1024u, 2048u, 4096u})
         for (uint32_t num : {4u, 5u}) {          // loads get 4/8 or 5/8 of the period
             windowed_row<2>(a, n4, 256, period, period * num / 8);
             windowed_row<1>(a, n4, 256, period, period * num / 8);
         }
+}
+
+// The 4-read/3-write library shape with stream s moved up by s * step bytes: do the
+// seven accesses a lane issues at one offset meet in the same channel or bank?
+static void stagger(size_t n, size_t n4) {
+    const size_t slack = (size_t)8 << 20;                 // room for the largest shift of the last stream
+    char* raw[7];
+    for (int i = 0; i < 7; ++i) {
+        CHECK(hipMalloc((void**)&raw[i], n4 * 16 + slack));
+        CHECK(hipMemset(raw[i], 0, n4 * 16 + slack));
+    }
+    CHECK(hipDeviceSynchronize());
+    std::printf("4 reads + 3 writes, library shape (256 threads x 2 groups), streams of %zu floats;\n"
+                "stream s starts s * step bytes into its own allocation; median of 11 launches\n", n);
+    const size_t steps[] = {0, 256, 1024, 4096, 4096 + 256, 16384, 65536, 65536 + 4096, 262144, 1 << 20,
+                            (1 << 20) + 4096 + 256, 0};
+    for (size_t step : steps) {
+        Streams a;
+        for (int i = 0; i < 4; ++i) a.r[i] = reinterpret_cast<const f32x4*>(raw[i] + (size_t)i * step);
+        for (int i = 0; i < 3; ++i) a.w[i] = reinterpret_cast<f32x4*>(raw[4 + i] + (size_t)(4 + i) * step);
+        a.w[3] = a.w[2];
+        const double bytes = 7.0 * (double)n4 * 16.0;
+        const unsigned grid = (unsigned)((n4 + 511) / 512);
+        const float t = median_of([&] {
+            hipLaunchKernelGGL((shape_kernel<2, 0>), dim3(grid), dim3(256), 0, 0, a, n4, 0.5f);
+        }, 11);
+        std::printf("step %8zu bytes   %6.1f us  %5.0f GB/s   (first allocation at %p, spacing of allocations %zd)\n",
+                    step, t * 1e3, bytes / t / 1e6, (void*)raw[0], (ptrdiff_t)(raw[1] - raw[0]));
+        std::fflush(stdout);
+    }
+    for (int i = 0; i < 7; ++i) CHECK(hipFree(raw[i]));
+}
+
+// The same launch over and over for about two seconds, timed in chunks: does the
+// rate settle, drift or step while the chip stays busy?
+static void sustain(Streams a, size_t n4) {
+    const double bytes = 7.0 * (double)n4 * 16.0;
+    const unsigned grid = (unsigned)((n4 + 511) / 512);
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    const int chunk = n4 > 20000000 ? 40 : 200;
+    std::printf("4 reads + 3 writes, library shape, back to back; GB/s per chunk of %d launches:\n", chunk);
+    double elapsed = 0.0;
+    for (int c = 0; c < 60 && elapsed < 2500.0; ++c) {
+        CHECK(hipEventRecord(e0));
+        for (int i = 0; i < chunk; ++i)
+            hipLaunchKernelGGL((shape_kernel<2, 0>), dim3(grid), dim3(256), 0, 0, a, n4, 0.5f);
+        CHECK(hipEventRecord(e1));
+        CHECK(hipEventSynchronize(e1));
+        float ms;
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        elapsed += ms;
+        std::printf("%5.0f", bytes * chunk / ms / 1e6);
+        if (c % 12 == 11) std::printf("   (%.0f ms)\n", elapsed);
+    }
+    std::printf("\n");
+    CHECK(hipGetLastError());
+    CHECK(hipEventDestroy(e0));
+    CHECK(hipEventDestroy(e1));
 }
 
 int main(int argc, char** argv) {
@@ -330,6 +441,10 @@ int main(int argc, char** argv) {
         return 2;
     }
     const size_t n4 = n / 4;
+    if (argc > 2 && std::string(argv[2]) == "stagger") {
+        stagger(n, n4);
+        return 0;
+    }
     Streams a;
     for (int i = 0; i < 4; ++i) {
         void* p;
@@ -341,6 +456,10 @@ int main(int argc, char** argv) {
         a.w[i] = static_cast<f32x4*>(p);
     }
     CHECK(hipDeviceSynchronize());
+    if (argc > 2 && std::string(argv[2]) == "sustain") {
+        sustain(a, n4);
+        return 0;
+    }
     if (argc > 2 && std::string(argv[2]) == "shapes") {
         std::printf("streams of %zu floats (%.1f MB each)\n", n, n4 * 16 / 1e6);
         shapes(a, n4);
