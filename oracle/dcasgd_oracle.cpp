@@ -52,8 +52,18 @@
 //
 // Pins (see tests/test_oracle_*.py): lambda = 0 gives ASGD (Eq. 2.2); M = 1
 // gives sequential SGD; exact-rational hand trace; closed forms for a
-// constant gradient; Philox known answers; Box-Muller against libm in
-// double; bf16 rounding against a library conversion.
+// constant gradient; Philox known answers and a second implementation on a
+// million counters; Box-Muller against libm in double and bit for bit against
+// a second implementation on numpy float32 arrays; bf16 rounding against a
+// library conversion; the state finite after every push of the benchmark
+// configurations; and single planted mistakes in a copy of this file, each of
+// which must fail a pin.
+// Parity unpinned (nothing in the paper fixes them; the pins only fix what is
+// computed): that ascending gradient norm is the fold order the supplement's
+// closing remark means; that heavy ball on the compensated gradient is the
+// authors' momentum rule; what bfloat16 snapshots do to the accuracy of a
+// real network; whether delay compensation helps on real networks at all
+// (the paper's evidence is CIFAR-10 / ImageNet accuracy).
 
 #include <cmath>
 #include <cstddef>
