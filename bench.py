@@ -347,6 +347,8 @@ def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: 
                            "algorithmic_bytes_per_launch": launch_bytes,
                            "bytes_per_element_update": bpu}
         valu = read_profile(pname, "valu_instr_per_launch")
+        if batched and arrivals_iid:
+            valu = None                  # the committed counters are of whole, unsplit queues
         # the same vector-issue peak at the engine clock and unit count this device reports
         props = torch.cuda.get_device_properties(dev)
         clock_hz = device_clock_hz(B.load(), dev.index or 0)
