@@ -264,6 +264,40 @@ __global__ void __launch_bounds__(256) share_kernel(Eight a, size_t n4, float k)
     }
 }
 
+// The push's bytes over fewer streams: two of the four read streams and two of the
+// three write streams are one stream each of twice the width, interleaved in runs of
+// 1 KiB (what w and MeanSquare would be if they shared one array), so that a wave
+// reads 2 KiB + 1 KiB + 1 KiB and writes 2 KiB + 1 KiB, all fully coalesced.
+template <bool MERGED>
+__global__ void __launch_bounds__(256) merged_kernel(const f32x4* a2, const f32x4* r1, const f32x4* r2,
+                                                     const f32x4* r3, f32x4* w2, f32x4* w1, f32x4* w0,
+                                                     size_t n4, float k) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const size_t q = (size_t)blockIdx.x * (blockDim.x * 2) + (size_t)j * blockDim.x + threadIdx.x;
+        if (q >= n4) continue;
+        const size_t run = q >> 6, lane = q & 63;
+        f32x4 x0, x1;
+        if (MERGED) {
+            x0 = ld<true>(a2 + (2 * run) * 64 + lane);
+            x1 = ld<true>(a2 + (2 * run + 1) * 64 + lane);
+        } else {
+            x0 = ld<true>(a2 + q);
+            x1 = ld<true>(r3 + q);
+        }
+        const f32x4 x2 = ld<true>(r1 + q), x3 = ld<true>(r2 + q);
+        const f32x4 acc = ((x0 * k + x1) * k + x2) * k + x3;
+        if (MERGED) {
+            st<true>(w2 + (2 * run) * 64 + lane, acc);
+            st<true>(w2 + (2 * run + 1) * 64 + lane, acc);
+        } else {
+            st<true>(w2 + q, acc);
+            st<true>(w0 + q, acc);
+        }
+        st<true>(w1 + q, acc);
+    }
+}
+
 template <class Launch> static float median_of(Launch&& launch, int reps) {
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0));
@@ -332,9 +366,12 @@ static void windowed_row(Streams a, size_t n4, int threads, uint32_t period, uin
 template <int R> static void share_row(Eight e, size_t n4) {
     const double bytes = 7.0 * (double)n4 * 16.0;
     const unsigned grid = (unsigned)((n4 + 511) / 512);
+    // settle first: a mix inherits the state the previous one left for tens of launches
+    for (int i = 0; i < 60; ++i)
+        hipLaunchKernelGGL((share_kernel<R>), dim3(grid), dim3(256), 0, 0, e, n4, 0.5f);
     const float t = median_of([&] {
         hipLaunchKernelGGL((share_kernel<R>), dim3(grid), dim3(256), 0, 0, e, n4, 0.5f);
-    }, 11);
+    }, 41);
     std::printf("%d read + %d write streams (%2.0f %% of the bytes written)   %6.1f us  %5.0f GB/s\n", R, 7 - R,
                 100.0 * (7 - R) / 7.0, t * 1e3, bytes / t / 1e6);
     std::fflush(stdout);
@@ -362,6 +399,38 @@ static void shapes(Streams a, size_t n4) {
     ahead_row<1, 0>("next tile's loads before this tile's stores, 8 per CU", a, n4, 256, 8, cus);
     ahead_row<4, 1>("the same, wave owns 4 KiB, 4 per CU", a, n4, 256, 4, cus);
     ahead_row<2, 0>("next tile's loads before this tile's stores, 16 per CU", a, n4, 128, 16, cus);
+    {
+        // n4 is rounded down to whole runs of 64 groups for this comparison
+        const size_t m4 = n4 & ~(size_t)63;
+        f32x4 *wide_r = nullptr, *wide_w = nullptr;
+        CHECK(hipMalloc((void**)&wide_r, 2 * m4 * 16));
+        CHECK(hipMalloc((void**)&wide_w, 2 * m4 * 16));
+        CHECK(hipMemset(wide_r, 0, 2 * m4 * 16));
+        CHECK(hipMemset(wide_w, 0, 2 * m4 * 16));
+        const double bytes = 7.0 * (double)m4 * 16.0;
+        const unsigned grid = (unsigned)((m4 + 511) / 512);
+        for (int merged = 0; merged < 2; ++merged) {
+            for (int i = 0; i < 40; ++i)
+                hipLaunchKernelGGL((merged_kernel<false>), dim3(grid), dim3(256), 0, 0, a.r[0], a.r[1], a.r[2],
+                                   a.r[3], a.w[0], a.w[1], a.w[2], m4, 0.5f);
+            const float t = median_of([&] {
+                if (merged)
+                    hipLaunchKernelGGL((merged_kernel<true>), dim3(grid), dim3(256), 0, 0,
+                                       (const f32x4*)wide_r, a.r[1], a.r[2], a.r[3], wide_w, a.w[1], a.w[2], m4,
+                                       0.5f);
+                else
+                    hipLaunchKernelGGL((merged_kernel<false>), dim3(grid), dim3(256), 0, 0, a.r[0], a.r[1],
+                                       a.r[2], a.r[3], a.w[0], a.w[1], a.w[2], m4, 0.5f);
+            }, 41);
+            std::printf("%-60s  %6.1f us  %5.0f GB/s\n",
+                        merged ? "the same bytes as 3 read + 2 write streams (two pairs share an array, 1 KiB runs)"
+                               : "4 read + 3 write streams, one group per lane and pass", t * 1e3,
+                        bytes / t / 1e6);
+            std::fflush(stdout);
+        }
+        CHECK(hipFree(wide_r));
+        CHECK(hipFree(wide_w));
+    }
     Eight e;
     for (int i = 0; i < 4; ++i) { e.p[i] = const_cast<f32x4*>(a.r[i]); e.p[4 + i] = a.w[i]; }
     std::printf("seven streams, 256 threads x 2 groups, all non-temporal, by share of writes:\n");
