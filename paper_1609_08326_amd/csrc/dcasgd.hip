@@ -45,14 +45,6 @@ void* scratch_on_current_device() {
 }
 }  // namespace
 
-// Build-time tuning of the queue kernel: entries per load group, and whether
-// the next group's loads are issued ahead of the current group's arithmetic.
-#ifndef DCASGD_BATCH_KC
-#define DCASGD_BATCH_KC 4
-#endif
-#ifndef DCASGD_BATCH_PIPE
-#define DCASGD_BATCH_PIPE 1
-#endif
 // Launches that can be timed between two dcasgd_timing_read calls; further
 // ones run untimed, so an unread handle does not pile up events.
 #define DCASGD_MAX_TIMED 65536
@@ -116,6 +108,16 @@ template <class F> inline void with_level(int v, F&& f) {
         case 1: f(std::integral_constant<int, 1>{}); break;
         default: f(std::integral_constant<int, 2>{}); break;
     }
+}
+// Load-group size of the queue kernel by queue length: a kernel built for
+// groups of 16 holds 32 float4 registers of loads per lane whatever the queue
+// brings, so short queues (and the pieces a queue with repeated workers is cut
+// into) get the kernels built for groups of 8 or 4, which keep more waves
+// resident.
+template <class F> inline void with_group(int K, F&& f) {
+    if (K >= 16) f(std::integral_constant<int, 16>{});
+    else if (K >= 8) f(std::integral_constant<int, 8>{});
+    else f(std::integral_constant<int, 4>{});
 }
 template <class F> inline void with_items(int v, F&& f) {
     switch (v) {
@@ -269,11 +271,12 @@ void launch_batch(dcasgd_t h, const int* workers, const void* const* grads, int 
       with_bool(h->grad_bf16, [&](auto BF) {
         with_bool(h->streaming != 0, [&](auto NT) {
           with_bool(h->bak_bf16, [&](auto BB) {
-            DCASGD_LAUNCH(h, (push_batch_kernel<decltype(AD)::value, decltype(MO)::value,
-                                                decltype(BF)::value, DCASGD_BATCH_KC,
-                                                decltype(NT)::value, (DCASGD_BATCH_PIPE != 0),
-                                                decltype(BB)::value>),
-                          grid, threads, s, h->hp, h->w, h->ms, a, n4, h->d);
+            with_group(a.K, [&](auto KC) {
+              DCASGD_LAUNCH(h, (push_batch_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                  decltype(BF)::value, decltype(KC)::value,
+                                                  decltype(NT)::value, decltype(BB)::value>),
+                            grid, threads, s, h->hp, h->w, h->ms, a, n4, h->d);
+            });
           });
         });
       });
