@@ -311,8 +311,9 @@ int dcasgd_set_lambda(dcasgd_t h, float lambda0);
  * finds them in the last-level cache when they fit; level 3 is the setting
  * that measures the update against HBM alone).  A zero/negative threads or
  * items keeps the current value.  Defaults: 256 threads (64 for the queue
- * kernel), 2 items (the push and pull kernels: 4 from d = 2^24 parameters
- * on), one block per tile, streaming 2.
+ * kernel); items by size (push and pull kernels: 2, the worker-fused push:
+ * 1, and 4 for both from d = 2^26 parameters on); one block per tile;
+ * streaming 2.
  */
 int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming);
 

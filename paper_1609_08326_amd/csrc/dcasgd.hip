@@ -69,8 +69,9 @@ struct dcasgd_server {
     hipStream_t stream = nullptr;     // stream of the most recent call that changed w (init, push*, fold*)
     uint64_t t = 0;                   // pushes applied (Algorithm 2's t)
     std::vector<uint64_t> fresh_at;   // t at which w_bak(m) was last set to w
-    int threads = 256, items = 2, max_blocks = 0;
-    int push_items = 2;               // items of the push and pull kernels (size rule in dcasgd_create)
+    int threads = 256, max_blocks = 0;
+    int items = 1;                    // float4 groups per lane of the worker-fused push
+    int push_items = 2;               // ... of the push and pull kernels (both set by size in dcasgd_create)
     int batch_threads = 64;           // the queue kernel does 16x the work per lane: one wave per block
     int streaming = 2;                // 0 plain, 1 gradient+backup non-temporal, 2 everything, 3 worker too
     int norm_blocks = 0;              // grid of the norm kernel, set by dcasgd_init
@@ -316,10 +317,14 @@ dcasgd_t dcasgd_create(size_t d, int M, float eta, float lambda0, int mode, floa
     h->pull_on_push = (flags & DCASGD_PULL_ON_PUSH) != 0;
     h->bak_bf16 = (flags & DCASGD_BAK_BF16) != 0;
     h->fresh_at.assign((size_t)M, 0);
-    // four float4 groups per lane once the vectors are large (measured: 2 % faster
-    // than two at 550 MB per vector, the same at 100 MB); small models keep more blocks
-    // (the worker-fused push, with three times the registers per group, keeps two)
-    h->push_items = d >= ((size_t)1 << 24) ? 4 : 2;
+    // four float4 groups per lane once the vectors dwarf the last-level cache (measured:
+    // 2 % faster than two at 550 MB per vector, 0-2 % slower at 100 MB)
+    h->push_items = d >= ((size_t)1 << 26) ? 4 : 2;
+    // the worker-fused push (three times the registers per group): one group per lane
+    // while the vectors are of the last-level cache's order, four once they dwarf it
+    // (measured: 131 / 135 / 137 us for 1 / 2 / 4 at 100 MB vectors, 822 / 786 / 754 us
+    // at 550 MB)
+    h->items = d >= ((size_t)1 << 26) ? 4 : 1;
     return h;
 }
 
