@@ -39,6 +39,9 @@ def test_create_validates_without_touching_a_gpu(lib):
     # not bound yet: every state-changing call is refused
     assert lib.dcasgd_init(ok, None) == B.ESTATE
     assert lib.dcasgd_push(ok, 0, None, None) == B.ESTATE
+    assert lib.dcasgd_sync_fold_ordered_static(ok, None, 1, 0.1, None) == B.ESTATE
+    assert lib.dcasgd_sync_fold_ordered_static(None, None, 1, 0.1, None) == B.EINVAL
+    assert lib.dcasgd_set_launch(ok, 0, 0, 0, 3) == B.OK and lib.dcasgd_set_launch(ok, 0, 0, 0, 4) == B.EINVAL
     assert not lib.dcasgd_pull(ok, 0)
     assert lib.dcasgd_last_error(ok) == B.ESTATE
     assert lib.dcasgd_bind(ok, None, None, 100, None) == B.EINVAL
