@@ -539,9 +539,11 @@ def leg_summary(rep: dict) -> dict:
                 if ceiling:
                     d["practical_ceiling_GBs"] = ceiling
                     d["frac_of_practical"] = r["achieved"] / ceiling
-    for k in ("native_loop_path", "fused_worker_path"):
+    for k in ("native_loop_path", "fused_worker_path", "ordered_fold_path"):
         if k in rep:
-            d[k] = {"value": rep[k]["value"], "ms_per_step": rep[k]["ms_per_step"]}
+            d[k] = {kk: vv for kk, vv in rep[k].items() if kk != "note"}
+    d["variant"] = rep["config"]["variant"]
+    d["snapshots"] = rep["config"]["snapshots"]
     return d
 
 
@@ -590,9 +592,11 @@ def main() -> int:
                     help="queued workload: fill the queues by independent uniform arrivals")
     ap.add_argument("--legs", default="default",
                     help="'default': after the headline region also the nothing-cached leg and "
-                         "one leg per other configuration (reported under all_configs) when the "
-                         "workload is the headline one and no variant flag is given; 'none': "
-                         "headline only; or a comma list of cfg0,cfg1,cfg2,cfg3,cfg3iid,cfg4,fold")
+                         "one leg per other configuration and further kernel (reported under "
+                         "all_configs) when the workload is the headline one and no variant flag "
+                         "is given; 'none': headline only; or a comma list of cfg0,cfg1,cfg2nc,cfg3,"
+                         "cfg3iid,cfg4,fold,cfg2_variant_c,cfg2_bf16_snapshots,cfg2_fused_worker,"
+                         "fold_ordered")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU oracle sample length; 0 skips the baseline")
     args = ap.parse_args()
@@ -610,7 +614,8 @@ def main() -> int:
                  args.iid_queues or args.no_events or args.threads or args.items or
                  args.max_blocks or args.streaming >= 0)
     if args.legs == "default":
-        legs = ["cfg2nc", "cfg3", "cfg3iid", "cfg4", "fold", "cfg0", "cfg1"] \
+        legs = ["cfg2nc", "cfg3", "cfg3iid", "cfg4", "fold", "cfg0", "cfg1",
+                "cfg2_variant_c", "cfg2_bf16_snapshots", "cfg2_fused_worker", "fold_ordered"] \
             if plain and wl.name.startswith("cfg2") else []
     elif args.legs == "none":
         legs = []
@@ -657,6 +662,18 @@ def main() -> int:
                     "worker's accesses non-temporal: every byte comes from and goes to HBM; it is "
                     "the figure to hold against an HBM-bandwidth target.")
             rep.pop("_wl", None)
+            continue
+        # further kernels at the headline size: the constant-lambda push, bfloat16 snapshots,
+        # the worker fused into the push, and the fold ranked by norm on the device
+        special = {"cfg2_variant_c": ("cfg2", dict(variant="c")),
+                   "cfg2_bf16_snapshots": ("cfg2", dict(bak_bf16=True)),
+                   "cfg2_fused_worker": ("cfg2", dict(fused_worker=True)),
+                   "fold_ordered": ("fold", dict(ordered=True))}
+        if leg in special:
+            name, overrides = special[leg]
+            rep = measure(leg_args(**overrides), name, ls, lw, extras=True)
+            rep.pop("_wl", None)
+            all_configs[leg] = leg_summary(rep)
             continue
         name = {"cfg3iid": "cfg3"}.get(leg, leg)
         rep = measure(leg_args(native_loop=small), name, ls, lw, arrivals_iid=(leg == "cfg3iid"),

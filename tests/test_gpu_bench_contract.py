@@ -55,7 +55,8 @@ def test_default_run_reports_every_configuration_and_the_cache_unassisted_fracti
     assert r["practical_ceiling_GBs"] is None or 0.8 < r["frac_of_practical"] < 1.25
     assert "traffic_source" in r and "which_is_hbm_only" in r
     legs = out["all_configs"]
-    assert sorted(legs) == ["cfg0", "cfg1", "cfg2", "cfg3", "cfg3iid", "cfg4", "fold"]
+    assert sorted(legs) == ["cfg0", "cfg1", "cfg2", "cfg2_bf16_snapshots", "cfg2_fused_worker",
+                            "cfg2_variant_c", "cfg3", "cfg3iid", "cfg4", "fold", "fold_ordered"]
     for name, leg in legs.items():
         assert leg["value"] > 0 and leg["workload"].startswith(name[:4]), name
         assert leg["avg_launch_ms"] > 0 and leg["bytes_per_element_update"] > 0, name
@@ -67,6 +68,10 @@ def test_default_run_reports_every_configuration_and_the_cache_unassisted_fracti
     assert legs["cfg3iid"]["value"] < legs["cfg3"]["value"]
     for name in ("cfg0", "cfg1"):
         assert legs[name]["native_loop_path"]["value"] > legs[name]["value"], name
+    assert legs["cfg2_variant_c"]["variant"] == "DC-ASGD-c" and legs["cfg2_variant_c"]["bytes_per_element_update"] == 20
+    assert legs["cfg2_bf16_snapshots"]["snapshots"] == "bf16" and legs["cfg2_bf16_snapshots"]["bytes_per_element_update"] == 24
+    assert legs["cfg2_fused_worker"]["fused_worker_path"]["value"] > legs["cfg2"]["value"]
+    assert legs["fold_ordered"]["ordered_fold_path"]["value"] < legs["fold"]["value"]
 
 
 def test_more_than_one_gpu_is_refused_on_the_box_too():
