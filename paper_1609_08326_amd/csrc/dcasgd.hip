@@ -112,13 +112,13 @@ template <class F> inline void with_level(int v, F&& f) {
 }
 // Load-group size of the queue kernel by queue length: a kernel built for
 // groups of 16 holds 32 float4 registers of loads per lane whatever the queue
-// brings, so short queues (and the pieces a queue with repeated workers is cut
-// into) get the kernels built for groups of 8 or 4, which keep more waves
-// resident.
+// brings; shorter queues (and the pieces a queue with repeated workers is cut
+// into) run the kernel built for groups of 8, 4, 2, 1.  (A third kernel built
+// for groups of at most 4 keeps more waves resident and measured 2 % slower on
+// pieces of about four entries.)
 template <class F> inline void with_group(int K, F&& f) {
     if (K >= 16) f(std::integral_constant<int, 16>{});
-    else if (K >= 8) f(std::integral_constant<int, 8>{});
-    else f(std::integral_constant<int, 4>{});
+    else f(std::integral_constant<int, 8>{});
 }
 template <class F> inline void with_items(int v, F&& f) {
     switch (v) {
