@@ -12,7 +12,10 @@
 // non-temporal accesses, what other ways of laying the same work over waves
 // and time achieve: longer contiguous runs per wave, lanes that own
 // consecutive groups, persistent blocks that have the next tile's loads in
-// flight while the current tile is stored, and launches whose waves issue
+// flight while the current tile is stored, the library's shape with the number
+// of resident blocks per compute unit capped by a claim of LDS that the kernel
+// never touches (a cap of 8 claims nothing: the hardware's own limit of
+// resident waves applies), and launches whose waves issue
 // their loads and their stores in alternating windows of the chip-wide
 // 100 MHz clock (every wait is on that free-running counter, never on another
 // wave, and gives up after a fixed number of polls).
@@ -377,6 +380,26 @@ template <int R> static void share_row(Eight e, size_t n4) {
     std::fflush(stdout);
 }
 
+template <int ITEMS> static void occupancy_rows(Streams a, size_t n4) {
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&shape_kernel<ITEMS, 0>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 163840));
+    const double bytes = 7.0 * (double)n4 * 16.0;
+    for (int threads : {64, 128, 256, 512})
+        for (unsigned per_cu : {8u, 4u, 2u, 1u}) {
+            const unsigned lds = per_cu >= 8 ? 0u : (163840u / per_cu) & ~1023u;
+            const size_t tile = (size_t)threads * ITEMS;
+            const unsigned grid = (unsigned)((n4 + tile - 1) / tile);
+            for (int i = 0; i < 20; ++i)
+                hipLaunchKernelGGL((shape_kernel<ITEMS, 0>), dim3(grid), dim3(threads), lds, 0, a, n4, 0.5f);
+            const float t = median_of([&] {
+                hipLaunchKernelGGL((shape_kernel<ITEMS, 0>), dim3(grid), dim3(threads), lds, 0, a, n4, 0.5f);
+            }, 21);
+            std::printf("library shape, %3d threads x %d groups, at most %u blocks per CU (%6u bytes of LDS claimed)"
+                        "  %6.1f us  %5.0f GB/s\n", threads, ITEMS, per_cu, lds, t * 1e3, bytes / t / 1e6);
+            std::fflush(stdout);
+        }
+}
+
 static void shapes(Streams a, size_t n4) {
     int dev = 0, cus = 0;
     CHECK(hipGetDevice(&dev));
@@ -431,6 +454,10 @@ static void shapes(Streams a, size_t n4) {
         CHECK(hipFree(wide_r));
         CHECK(hipFree(wide_w));
     }
+    // fewer resident blocks per compute unit (dynamic LDS the kernel never touches caps them)
+    occupancy_rows<2>(a, n4);
+    occupancy_rows<4>(a, n4);
+    occupancy_rows<8>(a, n4);
     Eight e;
     for (int i = 0; i < 4; ++i) { e.p[i] = const_cast<f32x4*>(a.r[i]); e.p[4 + i] = a.w[i]; }
     std::printf("seven streams, 256 threads x 2 groups, all non-temporal, by share of writes:\n");
