@@ -421,8 +421,8 @@ def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: 
                                     "note": "synthetic workload only: worker gradient formed in "
                                             "registers inside the push kernel"}
     if args.native_loop and K == 1 and not sync:
-        # the same arrivals through the library's own event loop (one C call, one fused
-        # launch per arrival)
+        # the same arrivals through the library's own event loop (one C call; one launch per
+        # block of 64 arrivals, the parameters staying in registers over the block)
         torch.cuda.synchronize()
         sv.run_synth(arrivals[:n_warm], hd, ws, wl.sigma, wl.seed)
         torch.cuda.synchronize()
@@ -430,10 +430,34 @@ def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: 
         sv.run_synth(arrivals[n_warm:n_warm + n_steps], hd, ws, wl.sigma, wl.seed)
         torch.cuda.synchronize()
         ne = time.perf_counter() - t0
+        # per arrival and parameter: the pusher's backup read and written; w, MeanSquare, h, w*
+        # read and w, MeanSquare written once per block of 64
+        b = 2 if args.bak_bf16 else 4
+        nbytes = 2 * b + ((16 if wl.mode == 1 else 12) + (8 if wl.mode == 1 else 4)) / 64.0
         out["native_loop_path"] = {"value": wl.d * n_steps / ne, "unit": "element-updates/s",
                                    "ms_per_step": 1e3 * ne / n_steps,
+                                   "bytes_per_element_update": nbytes,
+                                   "algorithmic_GBs": nbytes * wl.d * n_steps / ne / 1e9,
                                    "note": "synthetic workload only: dcasgd_run_synth, worker "
-                                           "fused into the push, launches issued from native code"}
+                                           "fused into the push, 64 arrivals per launch with w, "
+                                           "MeanSquare, h and w* held in registers"}
+        valu = read_profile("run_synth_blocks_%s" % wl.name.split("_")[0], "valu_instr_per_launch")
+        if valu and not args.bak_bf16 and not args.variant:
+            # counted over launches of 64 arrivals; wall clock of the whole call here
+            per_update = valu * 64 / (wl.d * 64.0)
+            lane_rate = per_update * wl.d * n_steps / ne / 1e12
+            out["native_loop_path"].update({
+                # 1 MB vectors give each SIMD one wave: the chains' latency, not issue, bounds them
+                "bound": "alu" if wl.d * 4 >= (16 << 20) else "instruction latency (one wave per SIMD)",
+                "valu_instr_per_element_update": per_update,
+                "alu_achieved_Tlane_per_s": lane_rate, "alu_peak_Tlane_per_s": VALU_PEAK_TLANE,
+                "alu_frac": lane_rate / VALU_PEAK_TLANE,
+                "alu_note": "the peak counts one wave instruction per SIMD every four cycles, "
+                            "which is what float32 add, multiply, fma, selects and integer "
+                            "multiplies take; adds, shifts, logic and moves on integers issue "
+                            "about twice as fast and sqrt/rcp/rsq half as fast "
+                            "(profiles/membw_probe_mi355x.txt, 'issue'), so a mix rich in the "
+                            "former can read above 1"})
     if args.ordered and sync:
         # norms + ranking + fold over the ranked list: three launches per fold
         fws = B.Server.fold_workspace(dev)
@@ -667,7 +691,7 @@ def main() -> int:
         # the worker fused into the push, and the fold ranked by norm on the device
         special = {"cfg2_variant_c": ("cfg2", dict(variant="c")),
                    "cfg2_bf16_snapshots": ("cfg2", dict(bak_bf16=True)),
-                   "cfg2_fused_worker": ("cfg2", dict(fused_worker=True)),
+                   "cfg2_fused_worker": ("cfg2", dict(fused_worker=True, native_loop=True)),
                    "fold_ordered": ("fold", dict(ordered=True))}
         if leg in special:
             name, overrides = special[leg]

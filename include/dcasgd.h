@@ -350,12 +350,21 @@ int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* w
 
 /*
  * The event loop of Algorithms 1 and 2 for the synthetic workload, driven from
- * native code: for e < T, dcasgd_push_synth(h, workers[e], ...), i.e. worker
- * workers[e] delivers the gradient of its snapshot, the server applies it and
- * (with DCASGD_PULL_ON_PUSH) hands the new model back.  workers: host array.
- * The whole list is validated before the first launch; one kernel launch per
- * arrival and no interpreter between them, which is what matters for small
- * models whose kernels run a few microseconds.
+ * native code: the state the call leaves is, bit for bit, that of
+ *   for e < T: dcasgd_push_synth(h, workers[e], hdiag, wstar, sigma, seed, stream)
+ * i.e. worker workers[e] delivers the gradient of its snapshot, the server
+ * applies it and (with DCASGD_PULL_ON_PUSH) hands the new model back.
+ * workers: host array, read before the call returns.  The whole list and the
+ * other arguments are validated before the first launch.  Both algorithms act
+ * on each parameter by itself, so the arrivals are not launched one by one:
+ * one launch covers up to 64 consecutive arrivals, each lane keeps its
+ * parameters of w, MeanSquare, hdiag and wstar in registers over them, and per
+ * arrival only the pusher's backup row is read and (with the fused pull)
+ * written - about 8 bytes per parameter and arrival instead of 32, and one
+ * launch per 64 arrivals, which is what matters for small models.  A worker
+ * may appear any number of times.  t advances by T; with a bound counter the
+ * noise is keyed at execution time as for dcasgd_push_synth.  (More than
+ * 65536 workers: arrival-by-arrival launches.)
  */
 int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdiag,
                      const float* wstar, float sigma, uint64_t seed, void* stream);

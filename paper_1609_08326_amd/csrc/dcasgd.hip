@@ -4,6 +4,7 @@
 // library owns is the static workspace declared below.
 #include "../../include/dcasgd.h"
 
+#include <algorithm>
 #include <cmath>
 #include <mutex>
 #include <new>
@@ -426,21 +427,27 @@ int dcasgd_push_batch(dcasgd_t h, const int* workers, const void* const* grads, 
     return launched(h);
 }
 
-int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* wstar, float sigma,
-                      uint64_t seed, void* stream) {
-    if (!h) return DCASGD_EINVAL;
-    if (!h->ready) return fail(h, DCASGD_ESTATE);
-    if (worker < 0 || worker >= h->M || !hdiag || !wstar || !std::isfinite(sigma))
-        return fail(h, DCASGD_EINVAL);
-    if (h->d > ((size_t)1 << 34) || h->t > 0xFFFFFFFFull) return fail(h, DCASGD_EINVAL);
-    if (!aligned(hdiag, 16) || !aligned(wstar, 16)) return fail(h, DCASGD_EALIGN);
+// what the worker-fused calls ask of the synthetic loss besides a valid worker
+static int check_synth_loss(dcasgd_t h, const float* hdiag, const float* wstar, float sigma) {
+    if (!hdiag || !wstar || !std::isfinite(sigma)) return DCASGD_EINVAL;
+    if (h->d > ((size_t)1 << 34)) return DCASGD_EINVAL;    // the counter holds i/4 in 32 bits
+    if (!aligned(hdiag, 16) || !aligned(wstar, 16)) return DCASGD_EALIGN;
     const size_t vb = h->d * 4, bb = bak_bytes(h);
     const void* loss[2] = {hdiag, wstar};
     for (const void* p : loss)
         if (overlaps(p, vb, h->w, vb) || overlaps(p, vb, h->bak, bb) ||
             (h->ms && overlaps(p, vb, h->ms, vb)) ||
             (h->hp.vel && overlaps(p, vb, h->hp.vel, vb)))
-            return fail(h, DCASGD_EINVAL);
+            return DCASGD_EINVAL;
+    return DCASGD_OK;
+}
+
+int dcasgd_push_synth(dcasgd_t h, int worker, const float* hdiag, const float* wstar, float sigma,
+                      uint64_t seed, void* stream) {
+    if (!h) return DCASGD_EINVAL;
+    if (!h->ready) return fail(h, DCASGD_ESTATE);
+    if (worker < 0 || worker >= h->M || h->t > 0xFFFFFFFFull) return fail(h, DCASGD_EINVAL);
+    if (int rc = check_synth_loss(h, hdiag, wstar, sigma)) return fail(h, rc);
     const size_t n4 = h->d / 4;
     void* row = bak_row(h, worker);
     const unsigned grid = grid_for(n4, (size_t)h->threads * h->items, h->max_blocks);
@@ -480,8 +487,52 @@ int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdia
     for (size_t e = 0; e < T; ++e)
         if (workers[e] < 0 || workers[e] >= h->M) return fail(h, DCASGD_EINVAL);
     if (h->t + T > 0xFFFFFFFFull) return fail(h, DCASGD_EINVAL);
-    for (size_t e = 0; e < T; ++e)
-        if (int rc = dcasgd_push_synth(h, workers[e], hdiag, wstar, sigma, seed, stream)) return rc;
+    if (int rc = check_synth_loss(h, hdiag, wstar, sigma)) return fail(h, rc);
+    if (T == 0) return DCASGD_OK;
+    if (h->M > 65536) {
+        // the block kernel names workers in 16 bits: beyond that, arrival by arrival
+        for (size_t e = 0; e < T; ++e)
+            if (int rc = dcasgd_push_synth(h, workers[e], hdiag, wstar, sigma, seed, stream)) return rc;
+        return DCASGD_OK;
+    }
+    // Blocks of up to RUN_BLOCK arrivals per launch; one float4 group per lane
+    // and pass, since a lane stays with its group for the whole block.
+    const size_t n4 = h->d / 4;
+    const int threads = n4 >= ((size_t)1 << 20) ? 256 : 64;
+    const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
+    const size_t row_bytes = h->bak_stride * bak_elem(h);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (size_t e0 = 0; e0 < T; e0 += RUN_BLOCK) {
+        const int A = (int)std::min<size_t>(RUN_BLOCK, T - e0);
+        Arrivals arr{};
+        for (int e = 0; e < A; ++e) arr.worker[e] = (uint16_t)workers[e0 + e];
+        const uint32_t push_idx = h->ctr ? 0u : (uint32_t)h->t;
+        with_bool(h->adaptive, [&](auto AD) {
+         with_bool(h->hp.vel != nullptr, [&](auto MO) {
+          with_bool(h->grad_bf16, [&](auto BF) {
+            with_bool(h->pull_on_push, [&](auto PL) {
+              with_bool(h->bak_bf16, [&](auto BB) {
+                with_bool(h->streaming != 0, [&](auto NT) {
+                  DCASGD_LAUNCH(h, (run_synth_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                     decltype(BF)::value, decltype(PL)::value,
+                                                     decltype(BB)::value, decltype(NT)::value>),
+                                grid, threads, s, h->hp, h->w, h->ms, h->bak, row_bytes, hdiag,
+                                wstar, sigma, k0, k1, push_idx, h->ctr, arr, A, n4, h->d);
+                });
+              });
+            });
+          });
+         });
+        });
+        advance_counter(h, (uint32_t)A, s);
+        h->stream = s;
+        for (int e = 0; e < A; ++e) {
+            h->t += 1;
+            if (h->pull_on_push) h->fresh_at[(size_t)workers[e0 + e]] = h->t;
+        }
+        if (int rc = launched(h)) return rc;
+    }
     return DCASGD_OK;
 }
 

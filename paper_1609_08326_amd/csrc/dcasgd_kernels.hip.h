@@ -173,7 +173,7 @@ __device__ __forceinline__ void apply_push(const Hyper& hp, float g, float b,
 // rescaling and special-value fix-ups of the general expansions.  While
 // operands and results stay far from both ends of the exponent range the
 // rescaling is the identity, so these give the same bits in ten instructions
-// instead of about thirty, and with ONE transcendental (quarter-rate)
+// instead of about thirty, and with ONE transcendental (half-rate)
 // instruction: the hardware estimate y of 1/sqrt(x) serves both steps.
 // Root: s = x*y (within a few ulps of sqrt(x)), its exact residual x - s*s,
 // and one Newton step with h = y/2.
@@ -979,6 +979,91 @@ push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
             if constexpr (ADAPTIVE) ms[i] = si;
             if constexpr (PULL) store_bak1<BB>(bak, i, wi);
             store_vel1<MOM>(hp, i, vi);
+        }
+    }
+}
+
+// ---- a block of arrivals of the synthetic workload in one pass ------------------
+// Algorithms 1 and 2 act on every parameter by itself, and for the synthetic
+// workload the arriving gradient is a function of state the lane already holds.
+// So a lane can keep its four parameters of w, MeanSquare, h and wstar in
+// registers over a whole block of arrivals and apply them one after the other
+// exactly as the arrival-by-arrival launches would (same operations in the
+// same order, hence the same bits); per arrival only the pusher's backup row
+// moves: 4 bytes read and, with the fused pull, 4 written per parameter
+// instead of 32.  The next arrival's backup is requested before the current
+// one is worked on; a worker that arrives twice in a row finds its backup in
+// registers, and one that returns later reads what this same lane stored
+// earlier in the launch (program order of one lane on one address).
+constexpr int RUN_BLOCK = 64;                 // arrivals per launch
+struct Arrivals { uint16_t worker[RUN_BLOCK]; };
+
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, bool BB, bool NT>
+__global__ void __launch_bounds__(256)
+run_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, void* bak,
+                 size_t row_bytes, const float* __restrict__ hdiag,
+                 const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
+                 uint32_t t_arg, const uint32_t* __restrict__ ctr, Arrivals arr, int A,
+                 size_t n4, size_t d) {
+    const uint32_t t0 = push_index(t_arg, ctr);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < n4; q += stride) {
+        f32x4 W = load4<NT>(w, q);
+        f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (ADAPTIVE) S = load4<NT>(ms, q);
+        const f32x4 H = load4<NT>(hdiag, q);
+        const f32x4 O = load4<NT>(wstar, q);
+        f32x4 V = load_vel4<MOM>(hp, q);
+        f32x4 B = load_bak4<BB, NT>(static_cast<char*>(bak) + arr.worker[0] * row_bytes, q);
+        for (int e = 0; e < A; ++e) {
+            void* row = static_cast<char*>(bak) + arr.worker[e] * row_bytes;
+            const bool more = e + 1 < A;
+            const bool again = more && arr.worker[e + 1] == arr.worker[e];
+            f32x4 Bn = B;
+            if (more && !again)
+                Bn = load_bak4<BB, NT>(static_cast<char*>(bak) + arr.worker[e + 1] * row_bytes, q);
+            const f32x4 z = normals_for_quad(k0, k1, t0 + (uint32_t)e, (uint32_t)q);
+            f32x4 g;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                g[c] = synth_delivered<BF16>(B[c], H[c], O[c], sigma, z[c]);
+            apply_push4<ADAPTIVE, MOM>(hp, g, B, W, S, V);
+            if constexpr (PULL) {
+                store_bak4<BB, NT>(row, q, W);
+                if (again) {
+                    // what a load of the row just stored would return
+                    if constexpr (BB) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) Bn[c] = widen_bf16(narrow_bf16(W[c]));
+                    } else {
+                        Bn = W;
+                    }
+                }
+            }
+            B = Bn;
+        }
+        store_vel4<MOM>(hp, q, V);
+        store4<NT>(w, q, W);
+        if constexpr (ADAPTIVE) store4<NT>(ms, q, S);
+    }
+    // ragged tail: the last, partial group of four shares one counter per arrival
+    if (blockIdx.x == 0 && threadIdx.x == 0 && 4 * n4 < d) {
+        for (int e = 0; e < A; ++e) {
+            void* row = static_cast<char*>(bak) + arr.worker[e] * row_bytes;
+            const f32x4 z = normals_for_quad(k0, k1, t0 + (uint32_t)e, (uint32_t)n4);
+            for (size_t i = 4 * n4; i < d; ++i) {
+                const float b = load_bak1<BB>(row, i);
+                const float g = synth_delivered<BF16>(b, hdiag[i], wstar[i], sigma, z[i - 4 * n4]);
+                float wi = w[i];
+                float si = 0.f;
+                if constexpr (ADAPTIVE) si = ms[i];
+                float vi = load_vel1<MOM>(hp, i);
+                apply_push<ADAPTIVE, MOM>(hp, g, b, wi, si, vi);
+                w[i] = wi;
+                if constexpr (ADAPTIVE) ms[i] = si;
+                if constexpr (PULL) store_bak1<BB>(row, i, wi);
+                store_vel1<MOM>(hp, i, vi);
+            }
         }
     }
 }

@@ -6,7 +6,7 @@
 // the DC-ASGD push is a 4-read/3-write stream, the pull a copy, the worker
 // kernel 3 reads and 1 write.
 //
-// usage: membw_probe [floats per stream, default 25557032] [shapes | stagger | sustain]
+// usage: membw_probe [floats per stream, default 25557032] [shapes | stagger | sustain | issue]
 // Allocates (4 + 4) buffers of that many floats; prints GB/s per pattern.
 // With "shapes" it prints instead, for the 4-read/3-write pattern with
 // non-temporal accesses, what other ways of laying the same work over waves
@@ -22,7 +22,9 @@
 // With "stagger" it shifts the seven streams of that pattern against each other
 // by multiples of a step, to see whether their relative placement matters;
 // with "sustain" it repeats that launch for about two seconds and prints the rate
-// over time.
+// over time; with "issue" it measures no memory at all but the rate at which
+// the vector ALUs take instructions of a few kinds (the other roof of the
+// kernels that do much arithmetic per byte).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -530,6 +532,104 @@ static void sustain(Streams a, size_t n4) {
     CHECK(hipEventDestroy(e1));
 }
 
+// ---- issue rate of the vector ALU -------------------------------------------
+// What "bound by arithmetic" can mean on this chip: eight independent chains per
+// lane of one instruction kind, nothing else in the loop but its counter.
+// Reported per kind and per number of resident waves: lane-instructions per
+// second over the whole chip, and the cycles of the device-reported clock that
+// one SIMD spends per wave instruction.
+enum IssueOp { OP_FMA, OP_MUL, OP_ADD, OP_MAD64, OP_MULLO, OP_RSQ, OP_SQRT, OP_RCP, OP_MULHI, OP_ADDU,
+               OP_XOR, OP_AND, OP_SHIFT, OP_MINU, OP_SELECT, OP_MOVE, OP_CONVERT };
+
+template <int OP>
+__global__ void __launch_bounds__(256) issue_kernel(float* out, float a, float b, uint32_t ua, int iters) {
+    float x[8];
+    uint32_t u[8];
+    uint64_t l[8];
+    const uint64_t mask = 0x5555555555555555ull * (uint64_t)(ua | 1u);   // lanes of a select, in scalar registers
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        x[i] = a + 0.125f * (float)i + 1e-3f * (float)threadIdx.x;
+        u[i] = ua * (uint32_t)(i + 1) + threadIdx.x;
+        l[i] = ((uint64_t)u[i] << 32) | (uint32_t)(threadIdx.x + i);
+    }
+#pragma unroll 8
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (OP == OP_FMA) x[i] = __builtin_fmaf(x[i], a, b);
+            if constexpr (OP == OP_MUL) x[i] = x[i] * a;
+            if constexpr (OP == OP_ADD) x[i] = x[i] + b;
+            if constexpr (OP == OP_MAD64) l[i] = (uint64_t)(uint32_t)l[i] * (uint64_t)ua + l[i];
+            if constexpr (OP == OP_MULLO) u[i] = u[i] * u[i];
+            if constexpr (OP == OP_MULHI) u[i] = __umulhi(u[i], u[i]);
+            if constexpr (OP == OP_ADDU) u[i] = u[i] + u[(i + 1) & 7];
+            // kinds the compiler would fold or fuse are written out (register operands only)
+            if constexpr (OP == OP_XOR) asm volatile("v_xor_b32 %0, %0, %1" : "+v"(u[i]) : "v"(ua));
+            if constexpr (OP == OP_AND) asm volatile("v_and_b32 %0, %0, %1" : "+v"(u[i]) : "v"(ua));
+            if constexpr (OP == OP_SHIFT) asm volatile("v_lshrrev_b32 %0, 1, %0" : "+v"(u[i]));
+            if constexpr (OP == OP_MINU) asm volatile("v_min_u32 %0, %0, %1" : "+v"(u[i]) : "v"(ua));
+            if constexpr (OP == OP_SELECT)
+                asm volatile("v_cndmask_b32_e64 %0, %0, %1, %2" : "+v"(u[i]) : "v"(ua), "s"(mask));
+            if constexpr (OP == OP_MOVE) asm volatile("v_mov_b32 %0, %1" : "=v"(u[i]) : "v"(ua));
+            if constexpr (OP == OP_CONVERT) asm volatile("v_cvt_f32_u32 %0, %0" : "+v"(u[i]));
+            if constexpr (OP == OP_RSQ) x[i] = __builtin_amdgcn_rsqf(x[i]);
+            if constexpr (OP == OP_SQRT) x[i] = __builtin_amdgcn_sqrtf(x[i]);
+            if constexpr (OP == OP_RCP) x[i] = __builtin_amdgcn_rcpf(x[i]);
+        }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += x[i] + (float)u[i] + (float)(uint32_t)(l[i] >> 32) + (float)(uint32_t)l[i];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
+
+template <int OP> static void issue_rows(const char* name, float* out, int cus, double clock_hz) {
+    const int iters = 20000;
+    for (int per_cu : {1, 2, 4, 8}) {                // 256-thread blocks: that many waves per SIMD
+        const unsigned grid = (unsigned)(cus * per_cu);
+        const float t = median_of([&] {
+            hipLaunchKernelGGL((issue_kernel<OP>), dim3(grid), dim3(256), 0, 0, out, 1.0000001f, 1e-9f,
+                               2654435761u, iters);
+        }, 9);
+        const double wave_instr = (double)grid * 4.0 * iters * 8.0;
+        std::printf("%-34s %d waves per SIMD  %8.1f us  %6.2f T lane-instr/s  %5.2f cycles per wave instruction and SIMD\n",
+                    name, per_cu, t * 1e3, wave_instr * 64.0 / (t * 1e-3) / 1e12,
+                    (double)cus * 4.0 * clock_hz * (t * 1e-3) / wave_instr);
+        std::fflush(stdout);
+    }
+}
+
+static void issue() {
+    int dev = 0, cus = 0, khz = 0;
+    CHECK(hipGetDevice(&dev));
+    CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    CHECK(hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev));
+    float* out;
+    CHECK(hipMalloc(&out, (size_t)cus * 8 * 256 * sizeof(float)));
+    std::printf("%d compute units, device-reported clock %.2f GHz; 8 independent chains per lane, 20000 x 8 instructions per lane\n",
+                cus, khz / 1e6);
+    const double hz = khz * 1e3;
+    issue_rows<OP_FMA>("v_fma_f32", out, cus, hz);
+    issue_rows<OP_MUL>("v_mul_f32", out, cus, hz);
+    issue_rows<OP_ADD>("v_add_f32", out, cus, hz);
+    issue_rows<OP_MAD64>("v_mad_u64_u32", out, cus, hz);
+    issue_rows<OP_MULLO>("v_mul_lo_u32", out, cus, hz);
+    issue_rows<OP_MULHI>("v_mul_hi_u32", out, cus, hz);
+    issue_rows<OP_ADDU>("v_add_u32", out, cus, hz);
+    issue_rows<OP_XOR>("v_xor_b32", out, cus, hz);
+    issue_rows<OP_AND>("v_and_b32", out, cus, hz);
+    issue_rows<OP_SHIFT>("v_lshrrev_b32", out, cus, hz);
+    issue_rows<OP_MINU>("v_min_u32", out, cus, hz);
+    issue_rows<OP_SELECT>("v_cndmask_b32 (mask in SGPRs)", out, cus, hz);
+    issue_rows<OP_MOVE>("v_mov_b32", out, cus, hz);
+    issue_rows<OP_CONVERT>("v_cvt_f32_u32", out, cus, hz);
+    issue_rows<OP_RSQ>("v_rsq_f32", out, cus, hz);
+    issue_rows<OP_SQRT>("v_sqrt_f32", out, cus, hz);
+    issue_rows<OP_RCP>("v_rcp_f32", out, cus, hz);
+    CHECK(hipFree(out));
+}
+
 int main(int argc, char** argv) {
     const size_t n = argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 25557032ull;
     if (n < 4 || n > (1ull << 32)) {
@@ -539,6 +639,10 @@ int main(int argc, char** argv) {
     const size_t n4 = n / 4;
     if (argc > 2 && std::string(argv[2]) == "stagger") {
         stagger(n, n4);
+        return 0;
+    }
+    if (argc > 2 && std::string(argv[2]) == "issue") {
+        issue();
         return 0;
     }
     Streams a;
