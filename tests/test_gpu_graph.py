@@ -52,8 +52,8 @@ def test_counter_bound_eager_path_matches_oracle(streaming):
     for m in order[1:5]:
         sv.worker_grad(int(m), hd, ws, wl.sigma, wl.seed, g)
         sv.push(int(m), g)
-    for m in order[5:]:
-        sv.push_synth(int(m), hd, ws, wl.sigma, wl.seed)
+    sv.push_synth(int(order[5]), hd, ws, wl.sigma, wl.seed)
+    sv.run_synth(order[6:], hd, ws, wl.sigma, wl.seed)            # the block kernel reads the counter too
     torch.cuda.synchronize()
     assert int(sv.counter.item()) == sv.t == len(order)
     ref = oracle.Server(wl.w0(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
@@ -61,7 +61,7 @@ def test_counter_bound_eager_path_matches_oracle(streaming):
     check(sv, ref, wl, "eager with device counter")
 
 
-@pytest.mark.parametrize("fused_worker", [False, True])
+@pytest.mark.parametrize("fused_worker", [False, True, "one launch for the block"])
 @pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
 def test_replayed_block_of_arrivals_keeps_matching_the_oracle(fused_worker, mode):
     import torch
@@ -76,6 +76,9 @@ def test_replayed_block_of_arrivals_keeps_matching_the_oracle(fused_worker, mode
     torch.cuda.synchronize()
 
     def one_block(sv):
+        if fused_worker == "one launch for the block":
+            sv.run_synth(block, hd, ws, wl.sigma, wl.seed)
+            return
         for m in block:
             if fused_worker:
                 sv.push_synth(int(m), hd, ws, wl.sigma, wl.seed)
