@@ -266,3 +266,18 @@ def test_blocks_of_arrivals_full_size_sampled(cfg):
     idx = wl.sample_indices(100_000, edge=4096)
     ref = oracle_run(wl, hd_h, ws_h, order, idx=idx, nthreads=16)
     check_blocks(sv, ref, wl, idx=idx)
+
+
+def test_more_workers_than_the_block_kernel_names_fall_back_to_single_launches():
+    """The block kernel names a worker in 16 bits; a server with more workers than that gets
+    the same arrivals launched one by one (tiny vectors, so 70000 backups are a few megabytes)."""
+    wl = small(6, 70000, 0, W.MODE_A, seed=37)
+    order = np.array([69999, 0, 65536, 69999, 69999, 65535, 1, 0, 65536, 3], dtype=np.int32)
+    sv, hd_h, ws_h = run_blocks(wl, order)
+    ref = oracle.Server(wl.w0(), wl.M, wl.eta, wl.lambda0, wl.mode, wl.ema_m, wl.eps)
+    ref.run(order, hd_h, ws_h, wl.sigma, wl.seed)
+    assert_same_bits(sv.w.cpu().numpy(), ref.w(), "many workers w")
+    assert_same_bits(sv.ms.cpu().numpy(), ref.ms(), "many workers ms")
+    rows = sv.bak[:, : wl.d].cpu().numpy()
+    for m in sorted(set(order.tolist())) + [2, 40000]:
+        assert_same_bits(rows[m], ref.bak(m), "many workers bak[%d]" % m)
