@@ -563,7 +563,7 @@ def leg_summary(rep: dict) -> dict:
                 if ceiling:
                     d["practical_ceiling_GBs"] = ceiling
                     d["frac_of_practical"] = r["achieved"] / ceiling
-    for k in ("native_loop_path", "fused_worker_path", "ordered_fold_path"):
+    for k in ("native_loop_path", "fused_worker_path", "ordered_fold_path", "graph_replay_path"):
         if k in rep:
             d[k] = {kk: vv for kk, vv in rep[k].items() if kk != "note"}
     d["variant"] = rep["config"]["variant"]
@@ -700,7 +700,8 @@ def main() -> int:
             all_configs[leg] = leg_summary(rep)
             continue
         name = {"cfg3iid": "cfg3"}.get(leg, leg)
-        rep = measure(leg_args(native_loop=small), name, ls, lw, arrivals_iid=(leg == "cfg3iid"),
+        rep = measure(leg_args(native_loop=small, graph=64 if small else 0), name, ls, lw,
+                      arrivals_iid=(leg == "cfg3iid"),
                       extras=small)
         rep.pop("_wl", None)
         all_configs[leg] = leg_summary(rep)

@@ -68,9 +68,14 @@ def test_default_run_reports_every_configuration_and_the_cache_unassisted_fracti
     assert legs["cfg3iid"]["value"] < legs["cfg3"]["value"]
     for name in ("cfg0", "cfg1"):
         assert legs[name]["native_loop_path"]["value"] > legs[name]["value"], name
+        # launch-bound eagerly: replayed from a graph faster, the block kernel faster still
+        assert legs[name]["value"] < legs[name]["graph_replay_path"]["value"] \
+            < legs[name]["native_loop_path"]["value"], name
     assert legs["cfg2_variant_c"]["variant"] == "DC-ASGD-c" and legs["cfg2_variant_c"]["bytes_per_element_update"] == 20
     assert legs["cfg2_bf16_snapshots"]["snapshots"] == "bf16" and legs["cfg2_bf16_snapshots"]["bytes_per_element_update"] == 24
     assert legs["cfg2_fused_worker"]["fused_worker_path"]["value"] > legs["cfg2"]["value"]
+    assert legs["cfg2_fused_worker"]["native_loop_path"]["value"] \
+        > legs["cfg2_fused_worker"]["fused_worker_path"]["value"]
     assert legs["fold_ordered"]["ordered_fold_path"]["value"] < legs["fold"]["value"]
 
 
