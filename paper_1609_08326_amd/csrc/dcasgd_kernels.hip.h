@@ -520,13 +520,22 @@ __device__ __forceinline__ void fold_quad(const Hyper& hp, float* __restrict__ w
     f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (ADAPTIVE) S = load4<false>(ms, q);
     f32x4 V = load_vel4<MOM>(hp, q);
+    // groups of KC gradients, the next group's loads issued before this group is worked on
     const int full = (J / KC) * KC;
-    for (int j0 = 0; j0 < full; j0 += KC) {
-        f32x4 G[KC];
+    f32x4 G[KC], N[KC];
+    if (full > 0) {
 #pragma unroll
-        for (int jj = 0; jj < KC; ++jj) G[jj] = load_grad4<BF16, NT>(gp[j0 + jj], q);
+        for (int jj = 0; jj < KC; ++jj) G[jj] = load_grad4<BF16, NT>(gp[jj], q);
+    }
+    for (int j0 = 0; j0 < full; j0 += KC) {
+        if (j0 + KC < full) {
+#pragma unroll
+            for (int jj = 0; jj < KC; ++jj) N[jj] = load_grad4<BF16, NT>(gp[j0 + KC + jj], q);
+        }
 #pragma unroll
         for (int jj = 0; jj < KC; ++jj) apply_push4<ADAPTIVE, MOM>(hp, G[jj], anchor, W, S, V);
+#pragma unroll
+        for (int jj = 0; jj < KC; ++jj) G[jj] = N[jj];
     }
     for (int j = full; j < J; ++j) {
         const f32x4 g = load_grad4<BF16, NT>(gp[j], q);
