@@ -1,7 +1,7 @@
 """Differential test of the whole C ABI as a state machine: a seeded random
 sequence of calls (pushes, queues with and without repeated workers, pulls,
-folds in the caller's order and ranked by norm (caller's and static workspace), worker-fused pushes, worker
-gradient + push, step-size and momentum changes) is applied to the library and,
+folds in the caller's order and ranked by norm (caller's and static workspace), worker-fused pushes, blocks
+of arrivals through the native event loop, worker gradient + push, step-size and momentum changes) is applied to the library and,
 call by call, to the oracle; every vector of the server state must agree bit
 for bit at checkpoints and at the end."""
 import sys
@@ -79,6 +79,8 @@ def test_random_call_sequence(seed):
            "worker_then_push", "eta", "momentum", "lambda", "fold_parts", "fold_static"]
     weights = np.array([4, 2, 1, 2, 1, 1, 2, 1, 1, 1, 1, 1, 1], dtype=float)
     trace = []
+    loop_rng = np.random.default_rng(5000 + seed)
+    lam_now = lam0
     for step in range(90):
         op = str(rng.choice(ops, p=weights / weights.sum()))
         trace.append(op)
@@ -161,11 +163,25 @@ def test_random_call_sequence(seed):
             lam = float(np.float32(rng.choice([0.0, 0.01, 0.04, 1.0, 2.0, 2.0 ** -45, -0.5])))
             sv.set_lambda(lam)
             ref.set_lambda(lam)
+            lam_now = lam
         elif op == "momentum":
             mu = float(np.float32(rng.choice([0.0, 0.5, 0.9])))
             torch.cuda.synchronize()          # the old velocity buffer is released here
             sv.set_momentum(mu)
             ref.set_momentum(mu)
+        if loop_rng.random() < 0.15 and lam_now >= 0.0:
+            # a block of arrivals through the native event loop (its own generator, so the
+            # calls above stay what they were before this one existed; not while lambda is
+            # negative: dozens of anti-compensated delayed steps in a row diverge)
+            trace.append("run_synth")
+            block = loop_rng.integers(0, M, int(loop_rng.integers(1, 70))).astype(np.int32)
+            sv.run_synth(block, hd, ws, wl.sigma, wl.seed)
+            if fused_pull:
+                ref.run(block, hd_h, ws_h, wl.sigma, wl.seed, as_bf16=bf16)
+            else:
+                for m in block:           # no pull: every gradient is taken at the standing backup
+                    ref.push(int(m), oracle.synth_grad(ref.bak(int(m)), hd_h, ws_h, wl.sigma,
+                                                       wl.seed, ref.t, as_bf16=bf16))
         if step % 23 == 22:
             check_state(sv, ref, M, d, "seed %d after %d calls (%s)" % (seed, step + 1, trace[-5:]))
     check_state(sv, ref, M, d, "seed %d at the end" % seed)
