@@ -314,8 +314,11 @@ int dcasgd_set_lambda(dcasgd_t h, float lambda0);
  * kernel); items by size (push and pull kernels: 2, the worker-fused push:
  * 1, and 4 for both from d = 2^26 parameters on); one block per tile;
  * streaming 2.  dcasgd_run_synth honours max_blocks and streaming (plain at
- * level 0, non-temporal otherwise) but chooses its own shape: one group per
- * lane, 64 threads per block below 2^20 groups and 256 from there on.
+ * level 0, non-temporal otherwise) but chooses its own shape: one float4 group
+ * per lane (two lanes per group for vectors shorter than 2^17 groups, which
+ * would otherwise leave most of the chip idle), 64 threads per block below
+ * 2^20 lanes and 256 from there on, and a block of its own for the d mod 4
+ * last parameters.
  */
 int dcasgd_set_launch(dcasgd_t h, int threads, int items, int max_blocks, int streaming);
 

@@ -52,6 +52,10 @@ void* scratch_on_current_device() {
 #ifndef DCASGD_FOLD_KC
 #define DCASGD_FOLD_KC 4      // gradients of a fold a lane loads before it starts on them
 #endif
+#ifndef DCASGD_RUN_PAIRS_BELOW
+#define DCASGD_RUN_PAIRS_BELOW (1 << 17)   // float4 groups below which the event loop gives a group two lanes
+                                           // (fewer than two waves per SIMD otherwise; measured equal at 2^17)
+#endif
 #ifndef DCASGD_NORM_ITEMS
 #define DCASGD_NORM_ITEMS 4   // float4 groups a lane of the norm kernel has in flight
 #endif
@@ -496,10 +500,15 @@ int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdia
         return DCASGD_OK;
     }
     // Blocks of up to RUN_BLOCK arrivals per launch; one float4 group per lane
-    // and pass, since a lane stays with its group for the whole block.
+    // and pass, since a lane stays with its group for the whole block.  Short
+    // vectors (fewer groups than give every SIMD a few waves) are cut finer:
+    // two lanes per group.
     const size_t n4 = h->d / 4;
-    const int threads = n4 >= ((size_t)1 << 20) ? 256 : 64;
-    const unsigned grid = grid_for(n4, (size_t)threads, h->max_blocks);
+    const bool pairs = n4 < (size_t)DCASGD_RUN_PAIRS_BELOW;
+    const size_t lanes = pairs ? 2 * n4 : n4;
+    const int threads = lanes >= ((size_t)1 << 20) ? 256 : 64;
+    // one more block when d is not a multiple of four: it does that tail and nothing else
+    const unsigned grid = grid_for(lanes, (size_t)threads, h->max_blocks) + (h->d % 4 ? 1u : 0u);
     const size_t row_bytes = h->bak_stride * bak_elem(h);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -514,11 +523,18 @@ int dcasgd_run_synth(dcasgd_t h, const int* workers, size_t T, const float* hdia
             with_bool(h->pull_on_push, [&](auto PL) {
               with_bool(h->bak_bf16, [&](auto BB) {
                 with_bool(h->streaming != 0, [&](auto NT) {
-                  DCASGD_LAUNCH(h, (run_synth_kernel<decltype(AD)::value, decltype(MO)::value,
-                                                     decltype(BF)::value, decltype(PL)::value,
-                                                     decltype(BB)::value, decltype(NT)::value>),
-                                grid, threads, s, h->hp, h->w, h->ms, h->bak, row_bytes, hdiag,
-                                wstar, sigma, k0, k1, push_idx, h->ctr, arr, A, n4, h->d);
+                  if (pairs)
+                      DCASGD_LAUNCH(h, (run_synth_pairs_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                               decltype(BF)::value, decltype(PL)::value,
+                                                               decltype(BB)::value, decltype(NT)::value>),
+                                    grid, threads, s, h->hp, h->w, h->ms, h->bak, row_bytes, hdiag,
+                                    wstar, sigma, k0, k1, push_idx, h->ctr, arr, A, n4, h->d);
+                  else
+                      DCASGD_LAUNCH(h, (run_synth_kernel<decltype(AD)::value, decltype(MO)::value,
+                                                         decltype(BF)::value, decltype(PL)::value,
+                                                         decltype(BB)::value, decltype(NT)::value>),
+                                    grid, threads, s, h->hp, h->w, h->ms, h->bak, row_bytes, hdiag,
+                                    wstar, sigma, k0, k1, push_idx, h->ctr, arr, A, n4, h->d);
                 });
               });
             });

@@ -1007,6 +1007,42 @@ push_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms,
 constexpr int RUN_BLOCK = 64;                 // arrivals per launch
 struct Arrivals { uint16_t worker[RUN_BLOCK]; };
 
+// The d mod 4 last parameters of a block of arrivals: one lane per parameter,
+// each forming only the normal it needs from the shared counter of the partial
+// group (word pair a,b for the first two parameters, c,d for the third; cosine
+// for even positions, sine for odd ones - what normals_for_quad hands out).
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, bool BB>
+__device__ __forceinline__ void run_synth_tail(const Hyper& hp, float* __restrict__ w,
+                                               float* __restrict__ ms, void* bak, size_t row_bytes,
+                                               const float* __restrict__ hdiag,
+                                               const float* __restrict__ wstar, float sigma,
+                                               uint32_t k0, uint32_t k1, uint32_t t0,
+                                               const Arrivals& arr, int A, size_t n4, size_t d) {
+    const size_t i = 4 * n4 + threadIdx.x;
+    if (i >= d) return;
+    const bool second_pair = threadIdx.x >= 2, odd = (threadIdx.x & 1) != 0;
+    float wi = w[i];
+    float si = 0.f;
+    if constexpr (ADAPTIVE) si = ms[i];
+    float vi = load_vel1<MOM>(hp, i);
+    const float hi = hdiag[i], oi = wstar[i];
+    for (int e = 0; e < A; ++e) {
+        void* row = static_cast<char*>(bak) + arr.worker[e] * row_bytes;
+        const Words4 x = philox10((uint32_t)n4, t0 + (uint32_t)e, 0u, 0u, k0, k1);
+        const float r = radius_from_word(second_pair ? x.c : x.a);
+        float co, sn;
+        circle_from_word(second_pair ? x.d : x.b, co, sn);
+        const float z = r * (odd ? sn : co);
+        const float b = load_bak1<BB>(row, i);
+        const float g = synth_delivered<BF16>(b, hi, oi, sigma, z);
+        apply_push<ADAPTIVE, MOM>(hp, g, b, wi, si, vi);
+        if constexpr (PULL) store_bak1<BB>(row, i, wi);
+    }
+    w[i] = wi;
+    if constexpr (ADAPTIVE) ms[i] = si;
+    store_vel1<MOM>(hp, i, vi);
+}
+
 template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, bool BB, bool NT>
 __global__ void __launch_bounds__(256)
 run_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, void* bak,
@@ -1015,8 +1051,13 @@ run_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, void* 
                  uint32_t t_arg, const uint32_t* __restrict__ ctr, Arrivals arr, int A,
                  size_t n4, size_t d) {
     const uint32_t t0 = push_index(t_arg, ctr);
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < n4; q += stride) {
+    // the d mod 4 last parameters are a whole block of arrivals of scalar work: they get a
+    // block of their own (the last one), so that no lane has two shares
+    const bool has_tail = 4 * n4 < d;
+    const size_t main_blocks = gridDim.x - (has_tail ? 1u : 0u);
+    const bool tail_block = has_tail && blockIdx.x == main_blocks;
+    const size_t stride = main_blocks * blockDim.x;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; !tail_block && q < n4; q += stride) {
         f32x4 W = load4<NT>(w, q);
         f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
         if constexpr (ADAPTIVE) S = load4<NT>(ms, q);
@@ -1055,26 +1096,123 @@ run_synth_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, void* 
         store4<NT>(w, q, W);
         if constexpr (ADAPTIVE) store4<NT>(ms, q, S);
     }
-    // ragged tail: the last, partial group of four shares one counter per arrival
-    if (blockIdx.x == 0 && threadIdx.x == 0 && 4 * n4 < d) {
+    if (tail_block)
+        run_synth_tail<ADAPTIVE, MOM, BF16, PULL, BB>(hp, w, ms, bak, row_bytes, hdiag, wstar, sigma,
+                                                      k0, k1, t0, arr, A, n4, d);
+}
+
+// The same loop for vectors too short to give every SIMD several waves at four
+// parameters per lane (the 1 MB configurations: one wave per SIMD, and the
+// dependent chains of Philox, Box-Muller and Eq. 18 leave it idle most of the
+// time).  Here two lanes share a group of four: both draw the group's Philox
+// words, each forms one of its two normal pairs and updates two parameters.
+// Twice the waves for about 1.15 times the instructions; the arithmetic per
+// parameter is unchanged, so the bits are.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+
+template <bool NT>
+__device__ __forceinline__ f32x2 load2(const float* base, size_t pair) {
+    const f32x2* p = reinterpret_cast<const f32x2*>(base) + pair;
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void store2(float* base, size_t pair, f32x2 v) {
+    f32x2* p = reinterpret_cast<f32x2*>(base) + pair;
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+template <bool BB, bool NT>
+__device__ __forceinline__ f32x2 load_bak2(const void* bak, size_t pair) {
+    if constexpr (BB) {
+        const u16x2* p = reinterpret_cast<const u16x2*>(bak) + pair;
+        u16x2 r;
+        if constexpr (NT) r = __builtin_nontemporal_load(p);
+        else r = *p;
+        return f32x2{widen_bf16(r.x), widen_bf16(r.y)};
+    } else {
+        return load2<NT>(reinterpret_cast<const float*>(bak), pair);
+    }
+}
+template <bool BB, bool NT>
+__device__ __forceinline__ void store_bak2(void* bak, size_t pair, f32x2 v) {
+    if constexpr (BB) {
+        const u16x2 r = {narrow_bf16(v.x), narrow_bf16(v.y)};
+        u16x2* p = reinterpret_cast<u16x2*>(bak) + pair;
+        if constexpr (NT) __builtin_nontemporal_store(r, p);
+        else *p = r;
+    } else {
+        store2<NT>(reinterpret_cast<float*>(bak), pair, v);
+    }
+}
+
+// a pair seen by the four-wide update: both halves hold the same two values, so
+// the duplicate arithmetic is one computation to the compiler
+__device__ __forceinline__ f32x4 twice(f32x2 a) { return f32x4{a.x, a.y, a.x, a.y}; }
+
+template <bool ADAPTIVE, bool MOM, bool BF16, bool PULL, bool BB, bool NT>
+__global__ void __launch_bounds__(256)
+run_synth_pairs_kernel(Hyper hp, float* __restrict__ w, float* __restrict__ ms, void* bak,
+                       size_t row_bytes, const float* __restrict__ hdiag,
+                       const float* __restrict__ wstar, float sigma, uint32_t k0, uint32_t k1,
+                       uint32_t t_arg, const uint32_t* __restrict__ ctr, Arrivals arr, int A,
+                       size_t n4, size_t d) {
+    const uint32_t t0 = push_index(t_arg, ctr);
+    const bool has_tail = 4 * n4 < d;                  // the last block does the d mod 4 tail only
+    const size_t main_blocks = gridDim.x - (has_tail ? 1u : 0u);
+    const bool tail_block = has_tail && blockIdx.x == main_blocks;
+    const size_t stride = main_blocks * blockDim.x;
+    const size_t npairs = 2 * n4;                      // pair p holds parameters 2p, 2p+1 of group p/2
+    for (size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x; !tail_block && p < npairs; p += stride) {
+        const bool upper = (p & 1) != 0;
+        // the lane's state is two values per vector; they are doubled for the four-wide
+        // update inside each iteration, never across iterations (loop-carried copies
+        // would be updated twice)
+        f32x2 W = load2<NT>(w, p);
+        f32x2 S = f32x2{0.f, 0.f};
+        if constexpr (ADAPTIVE) S = load2<NT>(ms, p);
+        const f32x2 H = load2<NT>(hdiag, p);
+        const f32x2 O = load2<NT>(wstar, p);
+        f32x2 V = f32x2{0.f, 0.f};
+        if constexpr (MOM) V = load2<true>(hp.vel, p);
+        f32x2 B = load_bak2<BB, NT>(static_cast<char*>(bak) + arr.worker[0] * row_bytes, p);
         for (int e = 0; e < A; ++e) {
             void* row = static_cast<char*>(bak) + arr.worker[e] * row_bytes;
-            const f32x4 z = normals_for_quad(k0, k1, t0 + (uint32_t)e, (uint32_t)n4);
-            for (size_t i = 4 * n4; i < d; ++i) {
-                const float b = load_bak1<BB>(row, i);
-                const float g = synth_delivered<BF16>(b, hdiag[i], wstar[i], sigma, z[i - 4 * n4]);
-                float wi = w[i];
-                float si = 0.f;
-                if constexpr (ADAPTIVE) si = ms[i];
-                float vi = load_vel1<MOM>(hp, i);
-                apply_push<ADAPTIVE, MOM>(hp, g, b, wi, si, vi);
-                w[i] = wi;
-                if constexpr (ADAPTIVE) ms[i] = si;
-                if constexpr (PULL) store_bak1<BB>(row, i, wi);
-                store_vel1<MOM>(hp, i, vi);
+            const bool more = e + 1 < A;
+            const bool again = more && arr.worker[e + 1] == arr.worker[e];
+            f32x2 Bn = B;
+            if (more && !again)
+                Bn = load_bak2<BB, NT>(static_cast<char*>(bak) + arr.worker[e + 1] * row_bytes, p);
+            const Words4 x = philox10((uint32_t)(p >> 1), t0 + (uint32_t)e, 0u, 0u, k0, k1);
+            const float r = radius_from_word(upper ? x.c : x.a);
+            float co, si;
+            circle_from_word(upper ? x.d : x.b, co, si);
+            const f32x2 z = {r * co, r * si};
+            f32x2 g;
+            g.x = synth_delivered<BF16>(B.x, H.x, O.x, sigma, z.x);
+            g.y = synth_delivered<BF16>(B.y, H.y, O.y, sigma, z.y);
+            f32x4 W4 = twice(W), S4 = twice(S), V4 = twice(V);
+            apply_push4<ADAPTIVE, MOM>(hp, twice(g), twice(B), W4, S4, V4);
+            W = f32x2{W4.x, W4.y};
+            S = f32x2{S4.x, S4.y};
+            V = f32x2{V4.x, V4.y};
+            if constexpr (PULL) {
+                store_bak2<BB, NT>(row, p, W);
+                if (again) {
+                    if constexpr (BB) Bn = f32x2{widen_bf16(narrow_bf16(W.x)), widen_bf16(narrow_bf16(W.y))};
+                    else Bn = W;
+                }
             }
+            B = Bn;
         }
+        if constexpr (MOM) store2<true>(hp.vel, p, V);
+        store2<NT>(w, p, W);
+        if constexpr (ADAPTIVE) store2<NT>(ms, p, S);
     }
+    if (tail_block)
+        run_synth_tail<ADAPTIVE, MOM, BF16, PULL, BB>(hp, w, ms, bak, row_bytes, hdiag, wstar, sigma,
+                                                      k0, k1, t0, arr, A, n4, d);
 }
 
 }  // namespace dcasgd

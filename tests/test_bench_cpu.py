@@ -33,9 +33,10 @@ def test_profile_figures_are_read_from_the_committed_summaries():
     assert bench.read_profile("push_fused_cfg2") > 7.0e8
     assert bench.read_profile("sync_fold_J16_fold", "valu_instr_per_launch") > 1e8
     # the event loop's kernel: per launch of 64 arrivals, about 90 instructions per update
+    # (about 105 at the 1 MB size, where two lanes share a group and both draw its Philox words)
     for cfg, d in (("cfg1", 272_474), ("cfg2", 25_557_032), ("cfg4", 138_357_544)):
         valu = bench.read_profile("run_synth_blocks_%s" % cfg, "valu_instr_per_launch")
-        assert 80.0 < valu * 64 / (d * 64.0) < 100.0, cfg
+        assert 80.0 < valu * 64 / (d * 64.0) < 115.0, cfg
     assert bench.read_profile("no_such_kernel") is None
 
 

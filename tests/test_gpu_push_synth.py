@@ -281,3 +281,17 @@ def test_more_workers_than_the_block_kernel_names_fall_back_to_single_launches()
     rows = sv.bak[:, : wl.d].cpu().numpy()
     for m in sorted(set(order.tolist())) + [2, 40000]:
         assert_same_bits(rows[m], ref.bak(m), "many workers bak[%d]" % m)
+
+
+@pytest.mark.parametrize("mode", [W.MODE_C, W.MODE_A])
+def test_blocks_of_arrivals_both_lane_layouts_every_element(mode):
+    """Vectors shorter than 2^17 groups of four get two lanes per group, longer ones one lane per
+    group: one size on each side of the switch, and one just past it with a ragged tail, every
+    element compared."""
+    for d in ((1 << 19) - 4, 1 << 19, (1 << 19) + 7):
+        wl = small(d, 5, 100, mode, seed=41).replace(eta=0.05)
+        order = wl.arrivals()
+        say("run_synth blocks d=%d mode=%d" % (d, mode))
+        sv, hd_h, ws_h = run_blocks(wl, order)
+        ref = oracle_run(wl, hd_h, ws_h, order, nthreads=16)
+        check_blocks(sv, ref, wl)
