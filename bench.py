@@ -447,8 +447,8 @@ def measure(args, workload: str, n_steps: int, n_warm: int, *, uncached_worker: 
             per_update = valu * 64 / (wl.d * 64.0)
             lane_rate = per_update * wl.d * n_steps / ne / 1e12
             out["native_loop_path"].update({
-                # 1 MB vectors give each SIMD one wave: the chains' latency, not issue, bounds them
-                "bound": "alu" if wl.d * 4 >= (16 << 20) else "instruction latency (one wave per SIMD)",
+                # 1 MB vectors give each SIMD two waves: the chains' latency, not issue, bounds them
+                "bound": "alu" if wl.d * 4 >= (16 << 20) else "instruction latency (two waves per SIMD)",
                 "valu_instr_per_element_update": per_update,
                 "alu_achieved_Tlane_per_s": lane_rate, "alu_peak_Tlane_per_s": VALU_PEAK_TLANE,
                 "alu_frac": lane_rate / VALU_PEAK_TLANE,
