@@ -18,6 +18,10 @@
 
 #pragma clang fp contract(off)
 
+#ifndef DCASGD_SHORT_RADIUS
+#define DCASGD_SHORT_RADIUS true    // false: the noise radius through the general sqrt and divide
+#endif
+
 namespace dcasgd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -739,8 +743,17 @@ __device__ __forceinline__ Words4 philox10(uint32_t c0, uint32_t c1, uint32_t c2
 }
 
 // sqrt(-2 ln u) for u = ((word >> 8) + 1) / 2^24, with ln through the atanh
-// series on the mantissa folded into (sqrt(1/2), sqrt(2)].
-__device__ __forceinline__ float radius_from_word(uint32_t word) {
+// series on the mantissa folded into (sqrt(1/2), sqrt(2)].  The definition
+// asks for a correctly rounded division and square root.  SHORT = false takes
+// the compiler's general expansions (exponent rescaling, special values: 11
+// and 15 instructions).  SHORT = true takes six and seven: the operands of
+// this function are confined - the divisor lies in (1.7, 2.42), the radicand
+// is zero or lies in [2^-23, 34) - so a reciprocal or reciprocal-square-root
+// estimate, one Newton step and one residual correction suffice, and since
+// the function has only 2^24 distinct inputs the claim "same bits" is checked
+// on every one of them (lambda_check radius).
+template <bool SHORT>
+__device__ __forceinline__ float radius_from_word_as(uint32_t word) {
     const float u = (float)((word >> 8) + 1u) * 0x1p-24f;
     const uint32_t ub = __float_as_uint(u);
     int ex = (int)(ub >> 23) - 127;
@@ -751,7 +764,17 @@ __device__ __forceinline__ float radius_from_word(uint32_t word) {
     ex = fold ? ex + 1 : ex;
     const float num = mant - 1.0f;
     const float den = mant + 1.0f;
-    const float s = num / den;
+    float s;
+    if constexpr (SHORT) {
+        float y = __builtin_amdgcn_rcpf(den);
+        const float e = __builtin_fmaf(-den, y, 1.0f);
+        y = __builtin_fmaf(e, y, y);
+        const float q = num * y;
+        const float r = __builtin_fmaf(-den, q, num);
+        s = __builtin_fmaf(r, y, q);
+    } else {
+        s = num / den;
+    }
     const float ss = s * s;
     float acc = 0.11111111f;
     acc = acc * ss; acc = acc + 0.14285715f;
@@ -763,7 +786,19 @@ __device__ __forceinline__ float radius_from_word(uint32_t word) {
     const float lne = (float)ex * 0.69314718f;
     const float lnu = lne + lnm;
     const float arg = -2.0f * lnu;
-    return __builtin_sqrtf(arg);
+    if constexpr (SHORT) {
+        const float y = __builtin_amdgcn_rsqf(arg);
+        const float t = arg * y;
+        const float h = 0.5f * y;
+        const float r = __builtin_fmaf(-t, t, arg);
+        const float root = __builtin_fmaf(r, h, t);
+        return arg == 0.0f ? arg : root;      // u = 1: the radicand is -0, and so is its root
+    } else {
+        return __builtin_sqrtf(arg);
+    }
+}
+__device__ __forceinline__ float radius_from_word(uint32_t word) {
+    return radius_from_word_as<DCASGD_SHORT_RADIUS>(word);
 }
 
 // (cos, sin) of 2*pi*j/2^24, j = word >> 8: fold to [0, pi/4], Taylor

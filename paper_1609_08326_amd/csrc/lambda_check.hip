@@ -24,6 +24,9 @@
 //                                      the pair is not admitted) - so that a host
 //                                      program can compare all four with its own CPU's
 //                                      IEEE operations
+//   lambda_check radius                the noise generator's radius sqrt(-2 ln u) in its short
+//                                      form against the form with the general divide and
+//                                      square root, on all 2^24 values of u
 // Prints the number of cases and of mismatches, the first few mismatches, and
 // exits non-zero if there is any.
 #include <hip/hip_runtime.h>
@@ -55,6 +58,16 @@ __device__ void note(Report* rep, uint32_t x, uint32_t a, float got, float want)
         rep->first[slot][2] = __float_as_uint(got);
         rep->first[slot][3] = __float_as_uint(want);
     }
+}
+
+// every input of the noise radius: k = word >> 8 in [0, 2^24)
+__global__ void check_radius(Report* rep) {
+    const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= (1u << 24)) return;
+    const uint32_t word = (k << 8) | (k & 0xFFu);      // the low byte does not enter
+    const float want = radius_from_word_as<false>(word);
+    const float got = radius_from_word_as<true>(word);
+    if (__float_as_uint(got) != __float_as_uint(want)) note(rep, word, 0u, got, want);
 }
 
 // radicand bits first .. first+count-1
@@ -195,6 +208,12 @@ int main(int argc, char** argv) {
             CHECK(hipDeviceSynchronize());
         }
         return finish("roots", total, rep);
+    }
+    if (!std::strcmp(argv[1], "radius")) {
+        hipLaunchKernelGGL(check_radius, dim3((1u << 24) / 256), dim3(256), 0, 0, rep);
+        CHECK(hipGetLastError());
+        CHECK(hipDeviceSynchronize());
+        return finish("radius", 1ull << 24, rep);
     }
     if (!std::strcmp(argv[1], "quotients") && argc >= 4) {
         const unsigned long long k_first = std::strtoull(argv[2], nullptr, 0);

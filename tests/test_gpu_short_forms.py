@@ -4,7 +4,8 @@ The stand-alone checker (built from the kernels' own header) compares those
 forms with the IEEE operations; here it runs on every admitted radicand, on
 every pair of radicand significand and numerator significand (1.4e14 cases,
 under a minute), on 2^34 random (radicand, numerator) pairs over the whole
-exponent window and both signs, and on the admission test itself."""
+exponent window and both signs, and on the admission test itself.  The noise
+generator's radius has a short form of its own, checked on all of its 2^24 inputs."""
 import os
 import subprocess
 import sys
@@ -31,6 +32,14 @@ def run(*args):
 def test_root_on_every_admitted_radicand():
     out = run("roots")
     assert "1073741824 cases" in out and " 0 mismatches" in out
+
+
+def test_noise_radius_short_form_on_every_input():
+    """sqrt(-2 ln u) with the reciprocal / reciprocal-square-root forms against the form with
+    the general divide and square root: the function has 2^24 inputs, all are compared.  (That
+    the general form is the oracle's arithmetic is what the worker-kernel parity tests show.)"""
+    out = run("radius")
+    assert "16777216 cases" in out and " 0 mismatches" in out
 
 
 def test_root_and_quotient_on_random_pairs_over_the_whole_range():
