@@ -267,7 +267,8 @@ int dcasgd_worker_grad(dcasgd_t h, int worker, const float* hdiag, const float* 
 
 /*
  * Per-launch timing of the server-update kernels (push, pull, push_batch,
- * push_synth, sync_fold).  While enabled, every such launch carries its own
+ * push_synth, sync_fold, and run_synth: one launch per block of up to 64
+ * arrivals).  While enabled, every such launch carries its own
  * start and stop HIP events, attached to the kernel itself, so their distance
  * is the kernel's execution time with no dispatch gap in it.  Events are host
  * objects created on demand and reused.  Do not enable it around launches

@@ -394,6 +394,10 @@ def test_per_launch_timing_counts_launches_and_changes_nothing():
     sv2.push(1, g)
     assert sv2.timing_read_each(capacity=1).size == 1     # a short buffer still ends the interval
     assert sv2.timing_read() == (0.0, 0)
+    # the event loop is timed per launch, i.e. per block of up to 64 arrivals
+    sv2.run_synth([0, 1, 2] * 50, hd, ws, wl.sigma, wl.seed)
+    each = sv2.timing_read_each()
+    assert each.size == 3 and np.all(each > 0.0)          # 64 + 64 + 22 arrivals
     # switching timing on again while timed launches are still in flight: their events are
     # handed out again, so the call first waits for them; the next interval is its own
     big = small(4_000_003, M=2, T=4)
